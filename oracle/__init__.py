@@ -1,0 +1,120 @@
+"""CPU oracle of the 8-bit optimizer step -- TEST INFRASTRUCTURE.
+
+Thin numpy/ctypes front end of oracle/q8_oracle.c (the arithmetic lives there).
+Only tests/, the smoke check and the benchmark's cpu_baseline leg may import it;
+it imports nothing from the HIP package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+
+from .build import build as _build
+
+FLAG_BIAS_CORRECTION = 1
+FLAG_DECOUPLED_WD = 2
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(_build())
+        fp, u8p, i64, i32, f32 = C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_float
+        L.oracle_build_codebook.argtypes = [i32, fp]
+        L.oracle_nearest_code.argtypes = [fp, f32]
+        L.oracle_nearest_code_bruteforce.argtypes = [fp, f32]
+        L.oracle_quantize_blockwise.argtypes = [fp, fp, i64, i32, u8p, fp]
+        L.oracle_dequantize_blockwise.argtypes = [fp, u8p, fp, i64, i32, fp]
+        L.oracle_adam32_step.argtypes = [fp, fp, fp, fp, i64, f32, f32, f32, f32, f32, i64, i32]
+        L.oracle_sgd32_step.argtypes = [fp, fp, fp, i64, f32, f32, f32]
+        L.oracle_adam8bit_step.argtypes = [fp, fp, u8p, u8p, fp, fp, fp, fp, i64, i32,
+                                           f32, f32, f32, f32, f32, i64, i32]
+        L.oracle_sgd8bit_step.argtypes = [fp, fp, u8p, fp, fp, i64, i32, f32, f32, f32]
+        for name in ("oracle_build_codebook", "oracle_nearest_code", "oracle_nearest_code_bruteforce",
+                     "oracle_quantize_blockwise", "oracle_dequantize_blockwise", "oracle_adam32_step",
+                     "oracle_sgd32_step", "oracle_adam8bit_step", "oracle_sgd8bit_step"):
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _p(a: np.ndarray, dtype) -> int:
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], (a.dtype, dtype)
+    return a.ctypes.data
+
+
+def _ok(rc):
+    if rc != 0:
+        raise ValueError("oracle call failed with status %d" % rc)
+
+
+def nblocks(n: int, B: int) -> int:
+    return (n + B - 1) // B
+
+
+def build_codebook(is_signed: bool) -> np.ndarray:
+    q = np.empty(256, np.float32)
+    _ok(lib().oracle_build_codebook(int(bool(is_signed)), _p(q, np.float32)))
+    return q
+
+
+def nearest_code(q: np.ndarray, x) -> int:
+    return lib().oracle_nearest_code(_p(q, np.float32), float(np.float32(x)))
+
+
+def nearest_code_bruteforce(q: np.ndarray, x) -> int:
+    return lib().oracle_nearest_code_bruteforce(_p(q, np.float32), float(np.float32(x)))
+
+
+def quantize_blockwise(q, T, B):
+    n = T.size
+    TQ = np.empty(n, np.uint8)
+    N = np.empty(nblocks(n, B), np.float32)
+    _ok(lib().oracle_quantize_blockwise(_p(q, np.float32), _p(T, np.float32), n, B,
+                                        _p(TQ, np.uint8), _p(N, np.float32)))
+    return TQ, N
+
+
+def dequantize_blockwise(q, TQ, N, B):
+    n = TQ.size
+    assert N.size == nblocks(n, B)
+    TD = np.empty(n, np.float32)
+    _ok(lib().oracle_dequantize_blockwise(_p(q, np.float32), _p(TQ, np.uint8), _p(N, np.float32), n, B,
+                                          _p(TD, np.float32)))
+    return TD
+
+
+def adam32_step(w, g, m, r, alpha, beta1, beta2, eps, wd=0.0, t=1, flags=0):
+    """In place on w, m, r."""
+    n = w.size
+    assert g.size == n and m.size == n and r.size == n
+    _ok(lib().oracle_adam32_step(_p(w, np.float32), _p(g, np.float32), _p(m, np.float32), _p(r, np.float32),
+                                 n, alpha, beta1, beta2, eps, wd, t, flags))
+
+
+def sgd32_step(w, g, m, alpha, beta, wd=0.0):
+    n = w.size
+    assert g.size == n and m.size == n
+    _ok(lib().oracle_sgd32_step(_p(w, np.float32), _p(g, np.float32), _p(m, np.float32), n, alpha, beta, wd))
+
+
+def adam8bit_step(w, g, m_q, r_q, N_m, N_r, q_signed, q_unsigned, B,
+                  alpha, beta1, beta2, eps, wd=0.0, t=1, flags=0):
+    """In place on w, m_q, r_q, N_m, N_r."""
+    n = w.size
+    assert g.size == n and m_q.size == n and r_q.size == n
+    assert N_m.size == nblocks(n, B) and N_r.size == nblocks(n, B)
+    _ok(lib().oracle_adam8bit_step(_p(w, np.float32), _p(g, np.float32), _p(m_q, np.uint8), _p(r_q, np.uint8),
+                                   _p(N_m, np.float32), _p(N_r, np.float32),
+                                   _p(q_signed, np.float32), _p(q_unsigned, np.float32), n, B,
+                                   alpha, beta1, beta2, eps, wd, t, flags))
+
+
+def sgd8bit_step(w, g, m_q, N_m, q_signed, B, alpha, beta, wd=0.0):
+    n = w.size
+    assert g.size == n and m_q.size == n and N_m.size == nblocks(n, B)
+    _ok(lib().oracle_sgd8bit_step(_p(w, np.float32), _p(g, np.float32), _p(m_q, np.uint8), _p(N_m, np.float32),
+                                  _p(q_signed, np.float32), n, B, alpha, beta, wd))
