@@ -1,0 +1,201 @@
+"""ctypes binding of libq8opt.so: same names as include/q8opt.h, argument marshalling only.
+
+PyTorch appears here only as the owner of device memory and streams: functions take
+torch CUDA tensors (or raw integer device addresses), check dtype/contiguity, and pass
+`data_ptr()` plus the current HIP stream to the C ABI.  There is no CPU fallback: if the
+library is missing, or a call returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libq8opt.so")
+
+FLAG_BIAS_CORRECTION = 1
+FLAG_DECOUPLED_WD = 2
+
+OK, EINVAL, EALIGN, EBLOCK, ELAUNCH, ENOMEM, ECODEBOOK = 0, -1, -2, -3, -4, -5, -6
+
+EXPORTS = (
+    "q8_status_str", "q8_build_codebook", "q8_qtable_bytes", "q8_build_qtable", "q8_host_nearest_code",
+    "q8_quantize_blockwise", "q8_dequantize_blockwise", "q8_adam8bit_step", "q8_sgd8bit_step",
+    "q8_plan_create", "q8_plan_destroy", "q8_multi_adam8bit_step", "q8_multi_sgd8bit_step",
+)
+
+
+class Q8Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_str(status)))
+
+
+class q8_tensor(C.Structure):
+    _fields_ = [("w", C.c_void_p), ("g", C.c_void_p), ("n", C.c_int64),
+                ("m_q", C.c_void_p), ("r_q", C.c_void_p), ("N_m", C.c_void_p), ("N_r", C.c_void_p),
+                ("m_f32", C.c_void_p), ("r_f32", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib():
+    """Load libq8opt.so (built by `python -m paper_2412_01195_amd.build` or __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libq8opt.so is not built (%s); run __graft_entry__.build()" % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int, C.c_float
+        L.q8_status_str.argtypes = [i32]; L.q8_status_str.restype = C.c_char_p
+        L.q8_build_codebook.argtypes = [i32, vp]
+        L.q8_qtable_bytes.argtypes = []; L.q8_qtable_bytes.restype = C.c_size_t
+        L.q8_build_qtable.argtypes = [vp, vp]
+        L.q8_host_nearest_code.argtypes = [vp, f32]
+        L.q8_quantize_blockwise.argtypes = [vp, vp, i64, i32, vp, vp, vp]
+        L.q8_dequantize_blockwise.argtypes = [vp, vp, vp, i64, i32, vp, vp]
+        L.q8_adam8bit_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, f32, f32, i64, i32, vp]
+        L.q8_sgd8bit_step.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
+        L.q8_plan_create.argtypes = [C.POINTER(q8_tensor), i32, i32, C.POINTER(vp)]
+        L.q8_plan_destroy.argtypes = [vp]
+        L.q8_multi_adam8bit_step.argtypes = [vp, vp, vp, f32, f32, f32, f32, f32, i64, i32, vp]
+        L.q8_multi_sgd8bit_step.argtypes = [vp, vp, f32, f32, f32, vp]
+        for name in EXPORTS:
+            if name not in ("q8_status_str", "q8_qtable_bytes"):
+                getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().q8_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != OK:
+        raise Q8Error(status, where)
+
+
+# ----------------------------------------------------------------------------- host side
+def build_codebook(is_signed: bool) -> np.ndarray:
+    q = np.empty(256, np.float32)
+    _check(lib().q8_build_codebook(int(bool(is_signed)), q.ctypes.data), "q8_build_codebook")
+    return q
+
+
+def qtable_bytes() -> int:
+    return int(lib().q8_qtable_bytes())
+
+
+def build_qtable(qmap: np.ndarray) -> np.ndarray:
+    """Host blob (uint8 array) to be copied to 16-byte aligned device memory."""
+    qmap = np.ascontiguousarray(qmap, np.float32)
+    if qmap.shape != (256,):
+        raise ValueError("qmap must hold 256 values")
+    blob = np.zeros(qtable_bytes(), np.uint8)
+    _check(lib().q8_build_qtable(qmap.ctypes.data, blob.ctypes.data), "q8_build_qtable")
+    return blob
+
+
+def host_nearest_code(qtable: np.ndarray, x) -> int:
+    assert qtable.dtype == np.uint8 and qtable.size == qtable_bytes()
+    c = lib().q8_host_nearest_code(qtable.ctypes.data, float(np.float32(x)))
+    if c < 0:
+        raise Q8Error(c, "q8_host_nearest_code")
+    return c
+
+
+# ----------------------------------------------------------------------------- device side
+def _ptr(t, dtype_name: Optional[str] = None) -> int:
+    """Device address of a torch CUDA tensor (or pass an int / None through)."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous CUDA tensor")
+    if dtype_name is not None and str(t.dtype) != "torch." + dtype_name:
+        raise ValueError("expected dtype %s, got %s" % (dtype_name, t.dtype))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def upload_qtable(blob: np.ndarray, device="cuda"):
+    """Copy a host qtable blob into a device uint8 tensor (torch allocations are 256-byte aligned)."""
+    import torch
+    return torch.from_numpy(blob).to(device)
+
+
+def quantize_blockwise(qtable, T, B: int, TQ, N, n: Optional[int] = None):
+    n = T.numel() if n is None else n
+    _check(lib().q8_quantize_blockwise(_ptr(qtable, "uint8"), _ptr(T, "float32"), n, B,
+                                       _ptr(TQ, "uint8"), _ptr(N, "float32"), _stream()), "q8_quantize_blockwise")
+
+
+def dequantize_blockwise(qtable, TQ, N, B: int, TD, n: Optional[int] = None):
+    n = TQ.numel() if n is None else n
+    _check(lib().q8_dequantize_blockwise(_ptr(qtable, "uint8"), _ptr(TQ, "uint8"), _ptr(N, "float32"), n, B,
+                                         _ptr(TD, "float32"), _stream()), "q8_dequantize_blockwise")
+
+
+def adam8bit_step(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, B: int,
+                  alpha, beta1, beta2, eps, weight_decay=0.0, t=1, flags=0, n: Optional[int] = None):
+    n = w.numel() if n is None else n
+    _check(lib().q8_adam8bit_step(_ptr(w, "float32"), _ptr(g, "float32"), _ptr(m_q, "uint8"), _ptr(r_q, "uint8"),
+                                  _ptr(N_m, "float32"), _ptr(N_r, "float32"),
+                                  _ptr(qtable_signed, "uint8"), _ptr(qtable_unsigned, "uint8"), n, B,
+                                  alpha, beta1, beta2, eps, weight_decay, t, flags, _stream()), "q8_adam8bit_step")
+
+
+def sgd8bit_step(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight_decay=0.0, n: Optional[int] = None):
+    n = w.numel() if n is None else n
+    _check(lib().q8_sgd8bit_step(_ptr(w, "float32"), _ptr(g, "float32"), _ptr(m_q, "uint8"), _ptr(N_m, "float32"),
+                                 _ptr(qtable_signed, "uint8"), n, B, alpha, beta, weight_decay, _stream()),
+           "q8_sgd8bit_step")
+
+
+class Plan:
+    """q8_plan: a list of parameter tensors updated by one launch.
+
+    Each entry is a dict with keys w, g and either (m_q, N_m[, r_q, N_r]) or (m_f32[, r_f32])."""
+
+    def __init__(self, tensors: Sequence[dict], B: int):
+        arr = (q8_tensor * len(tensors))()
+        self._keep = list(tensors)
+        for i, t in enumerate(tensors):
+            arr[i].w = _ptr(t["w"], "float32"); arr[i].g = _ptr(t["g"], "float32"); arr[i].n = t["w"].numel()
+            arr[i].m_q = _ptr(t.get("m_q"), "uint8"); arr[i].r_q = _ptr(t.get("r_q"), "uint8")
+            arr[i].N_m = _ptr(t.get("N_m"), "float32"); arr[i].N_r = _ptr(t.get("N_r"), "float32")
+            arr[i].m_f32 = _ptr(t.get("m_f32"), "float32"); arr[i].r_f32 = _ptr(t.get("r_f32"), "float32")
+        h = C.c_void_p()
+        _check(lib().q8_plan_create(arr, len(tensors), B, C.byref(h)), "q8_plan_create")
+        self._h = h
+
+    def multi_adam8bit_step(self, qtable_signed, qtable_unsigned, alpha, beta1, beta2, eps,
+                            weight_decay=0.0, t=1, flags=0):
+        _check(lib().q8_multi_adam8bit_step(self._h, _ptr(qtable_signed, "uint8"), _ptr(qtable_unsigned, "uint8"),
+                                            alpha, beta1, beta2, eps, weight_decay, t, flags, _stream()),
+               "q8_multi_adam8bit_step")
+
+    def multi_sgd8bit_step(self, qtable_signed, alpha, beta, weight_decay=0.0):
+        _check(lib().q8_multi_sgd8bit_step(self._h, _ptr(qtable_signed, "uint8"), alpha, beta, weight_decay,
+                                           _stream()), "q8_multi_sgd8bit_step")
+
+    def destroy(self):
+        if self._h:
+            _check(lib().q8_plan_destroy(self._h), "q8_plan_destroy")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass

@@ -1,0 +1,179 @@
+"""GPU parity of the stand-alone kernels and of the single-tensor steps against the CPU
+oracle, element by element: codes and absmax bit-exact, parameters within 1e-6 relative
+(the bar stated for this path).  Every call goes through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_01195_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def q8():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2412_01195_amd import q8opt
+    q8opt.lib()
+    return q8opt
+
+
+@pytest.fixture(scope="module")
+def tabs(q8):
+    ts = q8.upload_qtable(q8.build_qtable(q8.build_codebook(True)))
+    tu = q8.upload_qtable(q8.build_qtable(q8.build_codebook(False)))
+    return ts, tu
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def adversarial_tensor(q, n, B, rng):
+    """Random magnitudes per block plus values whose quotient by the block maximum sits on
+    codes, on code midpoints and one ulp around them."""
+    T = (rng.standard_normal(n) * 10.0 ** rng.uniform(-5, 1)).astype(np.float32)
+    nb = -(-n // B)
+    mids = ((q[:-1].astype(np.float64) + q[1:].astype(np.float64)) / 2).astype(np.float32)
+    special = np.concatenate([q, mids, np.nextafter(mids, np.float32(2)), np.nextafter(mids, np.float32(-2))])
+    for b in range(nb):
+        lo, hi = b * B, min(n, (b + 1) * B)
+        N = np.float32(2.0 ** rng.integers(-20, 8)) if b % 2 == 0 else np.abs(T[lo:hi]).max()
+        k = min(hi - lo, special.size)
+        pick = rng.choice(special, size=k, replace=False)
+        idx = rng.choice(hi - lo, size=k, replace=False)
+        blk = T[lo:hi]
+        blk[idx] = (pick * N).astype(np.float32)
+        blk[np.abs(blk) > N] = 0
+        if hi - lo > 1:
+            blk[rng.integers(0, hi - lo)] = N if b % 3 else -N       # negative arg-max in every third block
+    return T
+
+
+@pytest.mark.parametrize("signed", [True, False], ids=["signed", "unsigned"])
+@pytest.mark.parametrize("n,B", [(1, 64), (63, 64), (4097, 64), (1000, 128), (256 * 9 + 132, 256), (5000, 512),
+                                 (1024 * 3 + 1, 1024), (2048 * 5 + 512, 2048), (2047, 2048), (2048, 2048),
+                                 (4096 * 3 + 100, 4096), (300000, 2048), (300001, 256)])
+def test_quantize_dequantize_parity(q8, tabs, signed, n, B):
+    q = H.codebooks()[0 if signed else 1]
+    tab = tabs[0 if signed else 1]
+    rng = np.random.default_rng(n * 31 + B)
+    T = adversarial_tensor(q, n, B, rng)
+    if not signed and n > 10:
+        T = np.abs(T) if n % 2 else T            # unsigned map also sees negative inputs (clamped to code 0)
+    TQ_ref, N_ref = oracle.quantize_blockwise(q, T, B)
+    nb = oracle.nblocks(n, B)
+    TQ = torch.full((n,), 7, dtype=torch.uint8, device="cuda"); N = torch.full((nb,), -1.0, device="cuda")
+    q8.quantize_blockwise(tab, dev(T), B, TQ, N)
+    assert np.array_equal(N.cpu().numpy().view(np.uint32), N_ref.view(np.uint32))
+    got = TQ.cpu().numpy()
+    assert np.array_equal(got, TQ_ref), np.flatnonzero(got != TQ_ref)[:10]
+    TD = torch.empty(n, device="cuda")
+    q8.dequantize_blockwise(tab, TQ, N, B, TD)
+    assert np.array_equal(TD.cpu().numpy().view(np.uint32), oracle.dequantize_blockwise(q, TQ_ref, N_ref, B).view(np.uint32))
+
+
+def test_quantize_extreme_block_maxima(q8, tabs):
+    """Blocks whose maximum is tiny, huge, denormal or zero take the plain-divide path."""
+    q = H.codebooks()[0]
+    rng = np.random.default_rng(5)
+    B, nb = 256, 12
+    scales = [0.0, 1e-45, 1e-40, 1e-38, 2.0 ** -61, 2.0 ** -60, 2.0 ** -59, 2.0 ** 59, 2.0 ** 60, 2.0 ** 61, 1e38, 3e38]
+    T = np.concatenate([(rng.uniform(-1, 1, B) * s).astype(np.float32) for s in scales])
+    TQ_ref, N_ref = oracle.quantize_blockwise(q, T, B)
+    TQ = torch.empty(T.size, dtype=torch.uint8, device="cuda"); N = torch.empty(nb, device="cuda")
+    q8.quantize_blockwise(tabs[0], dev(T), B, TQ, N)
+    assert np.array_equal(N.cpu().numpy().view(np.uint32), N_ref.view(np.uint32))
+    assert np.array_equal(TQ.cpu().numpy(), TQ_ref)
+
+
+def run_adam(q8, tabs, n, B, steps, seed, std=1e-3, wd=0.0, flags=0, check_every=True):
+    w_ref = synth.uniform_weights(seed, 0, n)
+    st = H.zero_state(n, B)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    worst = 0.0
+    for t in range(1, steps + 1):
+        g = synth.normal_grad(seed, 0, t, n, std)
+        q8.adam8bit_step(w, dev(g), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B,
+                         **H.ADAM, weight_decay=wd, t=t, flags=flags)
+        H.oracle_adam8(w_ref, g, st, B, wd=wd, t=t, flags=flags)
+        if check_every or t == steps:
+            worst = max(worst, H.assert_state_equal("step %d" % t, d, st, w, w_ref))
+    return worst
+
+
+def run_sgd(q8, tabs, n, B, steps, seed, std=1e-2, wd=1e-4):
+    w_ref = synth.uniform_weights(seed, 0, n)
+    st = H.zero_state(n, B, adam=False)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    for t in range(1, steps + 1):
+        g = synth.normal_grad(seed, 0, t, n, std)
+        q8.sgd8bit_step(w, dev(g), d["m_q"], d["N_m"], tabs[0], B, **H.SGD, weight_decay=wd)
+        H.oracle_sgd8(w_ref, g, st, B, wd=wd)
+        H.assert_state_equal("step %d" % t, d, st, w, w_ref)
+
+
+@pytest.mark.parametrize("n,B", [(1, 2048), (5, 64), (2048, 2048), (2049, 2048), (4 * 2048 + 512, 2048),
+                                 (1000, 256), (6103 * 256 + 132, 256), (777, 128), (3 * 512 + 7, 512),
+                                 (5000, 1024), (3 * 4096 + 1, 4096)])
+def test_adam8bit_small_and_ragged(q8, tabs, n, B):
+    run_adam(q8, tabs, n, B, 6, seed=100 + B)
+
+
+@pytest.mark.parametrize("n,B", [(3, 2048), (2048 * 3 + 5, 2048), (1562500, 256), (700, 64), (9000, 4096)])
+def test_sgd8bit_small_and_ragged(q8, tabs, n, B):
+    run_sgd(q8, tabs, n, B, 6, seed=200 + B)
+
+
+def test_config1_adam_flat_1m(q8, tabs):
+    """Config 1: one flat tensor of 2^20 parameters, Adam, B = 2048, 10 steps from the zero state."""
+    worst = run_adam(q8, tabs, 1 << 20, 2048, 10, seed=1)
+    print("config 1: max parameter relative error %.3g" % worst)
+
+
+def test_adam_extension_flags(q8, tabs):
+    for flags, wd in ((0, 1e-2), (1, 0.0), (2, 0.05), (3, 0.05)):
+        run_adam(q8, tabs, 2048 * 3 + 77, 2048, 5, seed=300 + flags, wd=wd, flags=flags)
+
+
+def test_zero_gradient_keeps_zero_state(q8, tabs):
+    n, B = 5000, 2048
+    w0 = synth.uniform_weights(9, 0, n)
+    w = dev(w0); g = torch.zeros(n, device="cuda")
+    st = {k: dev(v) for k, v in H.zero_state(n, B).items()}
+    q8.adam8bit_step(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], tabs[0], tabs[1], B, **H.ADAM)
+    assert torch.all(st["m_q"] == 127) and torch.all(st["r_q"] == 0)
+    assert torch.all(st["N_m"] == 0) and torch.all(st["N_r"] == 0)
+    assert np.array_equal(w.cpu().numpy(), w0)
+
+
+def test_n_zero_and_errors_on_device(q8, tabs):
+    e = torch.empty(0, device="cuda"); eb = torch.empty(0, dtype=torch.uint8, device="cuda")
+    q8.adam8bit_step(e, e, eb, eb, e, e, tabs[0], tabs[1], 2048, **H.ADAM)
+    q8.sgd8bit_step(e, e, eb, e, tabs[0], 2048, **H.SGD)
+    w = torch.zeros(64, device="cuda")
+    with pytest.raises(q8.Q8Error) as err:
+        q8.sgd8bit_step(w, w, torch.zeros(64, dtype=torch.uint8, device="cuda"), torch.zeros(1, device="cuda"),
+                        tabs[0], 100, **H.SGD)
+    assert err.value.status == q8.EBLOCK
+    with pytest.raises(q8.Q8Error) as err:
+        q8.sgd8bit_step(w[1:], w[1:], torch.zeros(63, dtype=torch.uint8, device="cuda"),
+                        torch.zeros(1, device="cuda"), tabs[0], 64, **H.SGD)
+    assert err.value.status == q8.EALIGN
+
+
+def test_runs_on_the_callers_stream(q8, tabs):
+    n, B = 1 << 18, 2048
+    w_ref = synth.uniform_weights(11, 0, n); g = synth.normal_grad(11, 0, 1, n, 1e-3)
+    st = H.zero_state(n, B)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        w = dev(w_ref); gd = dev(g); d = {k: dev(v) for k, v in st.items()}
+        q8.adam8bit_step(w, gd, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM)
+    s.synchronize()
+    H.oracle_adam8(w_ref, g, st, B)
+    H.assert_state_equal("side stream", d, st, w, w_ref)

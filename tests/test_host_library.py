@@ -1,0 +1,126 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, its host
+functions (codebook, search table) agree with the oracle, and argument validation returns
+error codes before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_01195_amd import q8opt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "q8opt.h")).read()
+    declared = sorted(set(re.findall(r"Q8_API[^;]*?\b(q8_[a-z0-9_]+)\s*\(", hdr)))
+    assert declared == sorted(q8opt.EXPORTS)
+    L = q8opt.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert q8opt.status_str(0) == "Q8_OK" and "Q8_EBLOCK" in q8opt.status_str(q8opt.EBLOCK)
+
+
+@pytest.mark.parametrize("signed", [True, False])
+def test_codebook_bit_equal_to_oracle(signed):
+    assert np.array_equal(q8opt.build_codebook(signed).view(np.uint32), oracle.build_codebook(signed).view(np.uint32))
+
+
+def _critical_points(q):
+    pts = [np.float32(v) for v in (0.0, -0.0, 1.0, -1.0, 1e-45, -1e-45, 1e-38, 2.0 ** -24, 2.0 ** -25, -(2.0 ** -24))]
+    for j in range(256):
+        v = q[j]
+        for _ in range(3):
+            pts.append(v); v = np.nextafter(v, np.float32(2))
+        v = q[j]
+        for _ in range(3):
+            pts.append(v); v = np.nextafter(v, np.float32(-2))
+        if j < 255:
+            mid = np.float32((np.float64(q[j]) + np.float64(q[j + 1])) / 2)
+            lo = hi = mid
+            pts.append(mid)
+            for _ in range(4):
+                lo = np.nextafter(lo, np.float32(-2)); hi = np.nextafter(hi, np.float32(2))
+                pts += [lo, hi]
+    return [p for p in pts if abs(float(p)) <= 1.0]
+
+
+@pytest.mark.parametrize("signed", [True, False])
+def test_table_lookup_equals_oracle_search(signed):
+    q = oracle.build_codebook(signed)
+    tab = q8opt.build_qtable(q8opt.build_codebook(signed))
+    for x in _critical_points(q):
+        assert q8opt.host_nearest_code(tab, x) == oracle.nearest_code(q, x), float(x)
+    # every bucket edge of the table: all binary32 values with zero low mantissa bits, +-1 ulp
+    hdr = tab[:64].view(np.uint32)
+    M, shift = int(hdr[1]), int(hdr[2])
+    assert M == (6 if signed else 7)
+    keys = np.arange((127 - 26) << M, (127 << M) + 1, dtype=np.uint32) << np.uint32(shift)
+    for sign in (0, 0x80000000):
+        for d in (-1, 0, 1):
+            xs = ((keys + np.uint32(d & 0xFFFFFFFF)) | np.uint32(sign)).astype(np.uint32).view(np.float32)
+            for x in xs[np.abs(xs) <= 1]:
+                assert q8opt.host_nearest_code(tab, x) == oracle.nearest_code(q, x), float(x)
+    rng = np.random.default_rng(1)
+    xs = np.concatenate([rng.uniform(-1, 1, 20000), 10.0 ** rng.uniform(-10, 0, 20000) * rng.choice([-1, 1], 20000)])
+    for x in xs.astype(np.float32):
+        assert q8opt.host_nearest_code(tab, x) == oracle.nearest_code(q, x), float(x)
+
+
+def test_qtable_accepts_other_codebooks_and_rejects_bad_ones():
+    lin = np.linspace(-1, 1, 256).astype(np.float32)
+    tab = q8opt.build_qtable(lin)
+    rng = np.random.default_rng(2)
+    for x in rng.uniform(-1, 1, 5000).astype(np.float32):
+        assert q8opt.host_nearest_code(tab, x) == oracle.nearest_code(lin, x)
+    bad = lin.copy(); bad[10] = bad[9]
+    with pytest.raises(q8opt.Q8Error) as e:
+        q8opt.build_qtable(bad)
+    assert e.value.status == q8opt.ECODEBOOK
+    bad = lin.copy(); bad[255] = 1.5
+    with pytest.raises(q8opt.Q8Error):
+        q8opt.build_qtable(bad)
+    fine = np.sort(np.concatenate([[0.0], 1e-9 * np.arange(1, 256)])).astype(np.float32)   # too fine near zero
+    with pytest.raises(q8opt.Q8Error):
+        q8opt.build_qtable(fine)
+
+
+def test_argument_validation_needs_no_gpu():
+    L = q8opt.lib()
+    a = 0x1000  # fake, aligned, never dereferenced: validation fails first
+    assert L.q8_quantize_blockwise(a, a, -1, 2048, a, a, None) == q8opt.EINVAL
+    assert L.q8_quantize_blockwise(a, a, 10, 100, a, a, None) == q8opt.EBLOCK
+    assert L.q8_quantize_blockwise(a, a, 10, 32, a, a, None) == q8opt.EBLOCK
+    assert L.q8_quantize_blockwise(a, a, 10, 8192, a, a, None) == q8opt.EBLOCK
+    assert L.q8_quantize_blockwise(a, None, 10, 256, a, a, None) == q8opt.EINVAL
+    assert L.q8_quantize_blockwise(a, a + 4, 10, 256, a, a, None) == q8opt.EALIGN
+    assert L.q8_quantize_blockwise(a, a, 0, 256, a, a, None) == q8opt.OK          # n == 0: no-op
+    assert L.q8_dequantize_blockwise(a, a, a, 10, 256, a + 8, None) == q8opt.EALIGN
+    assert L.q8_dequantize_blockwise(a, a + 1, a, 10, 256, a, None) == q8opt.EALIGN
+    adam = lambda *p, n=10, B=2048, flags=0, t=1: L.q8_adam8bit_step(*p, n, B, 1e-3, 0.9, 0.999, 1e-8, 0.0, t, flags, None)
+    assert adam(a, a, a, a, a, a, a, a, n=-5) == q8opt.EINVAL
+    assert adam(a, a, a, a, a, a, a, a, B=1000) == q8opt.EBLOCK
+    assert adam(a, a, a, a, a, a, a, a, flags=8) == q8opt.EINVAL
+    assert adam(a, a, a, a, a, a, a, a, flags=1, t=0) == q8opt.EINVAL
+    assert adam(None, a, a, a, a, a, a, a) == q8opt.EINVAL
+    assert adam(a, a + 8, a, a, a, a, a, a) == q8opt.EALIGN
+    assert adam(a, a, a + 2, a, a, a, a, a) == q8opt.EALIGN
+    assert adam(a, a, a, a, a, a, a + 8, a) == q8opt.EALIGN
+    assert adam(a, a, a, a, a, a, a, a, n=0) == q8opt.OK
+    assert L.q8_sgd8bit_step(a, a, a, a, a, 10, 48, 0.1, 0.9, 0.0, None) == q8opt.EBLOCK
+    assert L.q8_sgd8bit_step(a, a, None, a, a, 10, 64, 0.1, 0.9, 0.0, None) == q8opt.EINVAL
+    assert L.q8_sgd8bit_step(a + 4, a, a, a, a, 10, 64, 0.1, 0.9, 0.0, None) == q8opt.EALIGN
+    h = C.c_void_p()
+    assert L.q8_plan_create(None, 1, 2048, C.byref(h)) == q8opt.EINVAL
+    t = (q8opt.q8_tensor * 1)()
+    t[0].w = a; t[0].g = a; t[0].n = 5
+    assert L.q8_plan_create(t, 1, 2048, C.byref(h)) == q8opt.EINVAL      # no state storage given
+    t[0].m_q = a; t[0].N_m = a + 2
+    assert L.q8_plan_create(t, 1, 2048, C.byref(h)) == q8opt.EALIGN
+    assert L.q8_plan_create(t, 0, 2048, C.byref(h)) == q8opt.EINVAL
+    assert L.q8_plan_create(t, 1, 3, C.byref(h)) == q8opt.EBLOCK
+    assert L.q8_plan_destroy(None) == q8opt.EINVAL
+    assert L.q8_multi_sgd8bit_step(None, a, 0.1, 0.9, 0.0, None) == q8opt.EINVAL
