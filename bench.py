@@ -91,6 +91,9 @@ def main():
     ap.add_argument("--workload", default="1b", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after timing, run one plain elementwise copy of the fp32 weights (4n bytes read, "
+                         "4n written) so that counter runs can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -134,6 +137,12 @@ def main():
     elapsed = time.perf_counter() - t0
     kern_ms = [a.elapsed_time(b) for a, b in ev]
     avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
+
+    if args.calibrate_copy:
+        scratch = torch.empty_like(g)
+        torch.mul(g, 1.0, out=scratch)
+        torch.cuda.synchronize()
+        del scratch
 
     alg = algorithmic_bytes(n, B)
     achieved = alg / avg_kern_s / 1e9

@@ -96,28 +96,30 @@ extern "C" q8_status q8_build_qtable(const float* qmap, void* qtable_out)
     }
     thr[255] = std::numeric_limits<float>::infinity();
 
-    for (int M = 3; M <= kMaxM; ++M) {
-        const uint32_t shift = 23 - M, kbase = (uint32_t)(127 - kMinExp) << M;
-        const uint32_t L = (uint32_t)kMinExp * (1u << M) + 1;
-        bool ok = true;
-        for (uint32_t i = 0; i < L && ok; ++i) {
-            uint32_t lo_bits = (i == 0) ? 0u : ((kbase + i) << shift);
-            uint32_t hi_bits = (i == L - 1) ? 0x3f800000u : (((kbase + i + 1) << shift) - 1);
-            float lo = bits_to_float(lo_bits), hi = bits_to_float(hi_bits);
-            int c0 = count_le(thr, lo), c1 = count_le(thr, hi);       // x >= 0
-            int n0 = count_le(thr, -hi), n1 = count_le(thr, -lo);     // x <= -0
-            if (c1 - c0 > 1 || n1 - n0 > 1) ok = false;
-            lut[i] = (unsigned char)c0;
-            lut[L + i] = (unsigned char)n0;
+    // Bucket table over all 65536 upper halves of a binary32 pattern.
+    const int code_p1 = count_le(thr, 1.0f), code_m1 = count_le(thr, -1.0f);
+    for (uint32_t key = 0; key < (uint32_t)kLutEntries; ++key) {
+        const bool neg = (key >> 15) != 0;
+        const uint32_t a = key & 0x7fffu;
+        int c;
+        if (a > kKeyOne) {                                  // |x| > 1, Inf, NaN: clamp
+            c = neg ? code_m1 : code_p1;
+        } else {
+            const float lo = bits_to_float(a << 16);
+            const float hi = (a == kKeyOne) ? 1.0f : bits_to_float((a << 16) | 0xffffu);
+            const int c0 = neg ? count_le(thr, -hi) : count_le(thr, lo);
+            const int c1 = neg ? count_le(thr, -lo) : count_le(thr, hi);
+            if (c1 - c0 > 1) return Q8_ECODEBOOK;          // two thresholds in one bucket
+            c = c0;
         }
-        if (!ok) continue;
-        QTabHeader h{};
-        h.magic = kMagic; h.M = (uint32_t)M; h.shift = shift; h.width = 8 + (uint32_t)M;
-        h.kbase = kbase; h.L = L; h.zero_code = (uint32_t)count_le(thr, 0.0f);
-        std::memcpy(blob, &h, sizeof h);
-        return Q8_OK;
+        lut[key] = (unsigned char)c;
     }
-    return Q8_ECODEBOOK;
+    QTabHeader h{};
+    h.magic = kMagic;
+    h.key_bits = 16;
+    h.zero_code = (uint32_t)count_le(thr, 0.0f);
+    std::memcpy(blob, &h, sizeof h);
+    return Q8_OK;
 }
 
 extern "C" int q8_host_nearest_code(const void* qtable, float x)
@@ -129,11 +131,7 @@ extern "C" int q8_host_nearest_code(const void* qtable, float x)
     if (h.magic != kMagic) return Q8_EINVAL;
     const float* thr = reinterpret_cast<const float*>(blob + kOffThr);
     const unsigned char* lut = blob + kOffLut;
-    uint32_t bits = float_to_bits(x);
-    uint32_t a = (bits >> h.shift) & ((1u << h.width) - 1);
-    int d = (int)a - (int)h.kbase;
-    int idx = d < 0 ? 0 : (d > (int)h.L - 1 ? (int)h.L - 1 : d);
-    if (bits >> 31) idx += (int)h.L;
+    const uint32_t idx = float_to_bits(x) >> 16;
     int c = lut[idx];
     return c + (x >= thr[c] ? 1 : 0);
 }

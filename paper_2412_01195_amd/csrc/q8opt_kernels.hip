@@ -8,8 +8,12 @@
 // 128-bit load/store per lane and every code access one coalesced 32-bit one.
 // New states stay in registers between the update and the re-quantization; the
 // block absmax needs only cross-lane DPP steps inside the wave (no barrier, no
-// LDS traffic).  Workgroups of 4 waves are persistent: they stage the two search
-// tables into LDS once and then walk over tiles with a grid stride.
+// LDS traffic).  Workgroups of 8 waves are persistent: they stage the search
+// tables into 64 KB of LDS once and then walk over tiles with a grid stride.
+//
+// Nearest-code search (Eq. quant2): the upper 16 bits of the binary32 pattern of
+// x = m / N index a byte table in LDS that holds the code at the lower end of that
+// bucket; one threshold read and one compare finish the decision exactly.
 //
 // Exact arithmetic: the update formulas are written one operation per statement
 // and the file is compiled with -ffp-contract=off.  The normalisation x = m / N
@@ -28,9 +32,24 @@ using namespace q8;
 
 namespace {
 
-constexpr int kWgThreads = 256;
-constexpr int kWavesPerWg = 4;
+constexpr int kWgThreads = 512;
+constexpr int kWavesPerWg = 8;
 constexpr int kRow = 256;                 // elements per wave row: 64 lanes x 4
+
+// Pointers into HBM carry the global address space so that loads and stores
+// are global_* instructions (a generic pointer would make them flat_*).
+#define Q8_GLOBAL __attribute__((address_space(1)))
+typedef Q8_GLOBAL float gfloat;
+typedef Q8_GLOBAL const float gcfloat;
+typedef Q8_GLOBAL uint8_t gbyte;
+typedef Q8_GLOBAL const uint8_t gcbyte;
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef Q8_GLOBAL v4f gfloat4;
+typedef Q8_GLOBAL const v4f gcfloat4;
+typedef Q8_GLOBAL uint32_t gu32;
+typedef Q8_GLOBAL const uint32_t gcu32;
+typedef Q8_GLOBAL const v4u gcuint4;
 
 struct TensorDesc {                       // device-side mirror of q8_tensor
     float* w;
@@ -48,53 +67,74 @@ struct TileRef { int32_t tensor; int32_t tile; };
 
 struct AdamScalars {
     float beta1, beta2, omb1, omb2, eps, wd, alpha_t, isbc2, alpha_wd;
-    int coupled_wd, decoupled_wd;
+    int wd_mode;                          // 0 none, 1 coupled (g += wd*w), 2 decoupled
 };
 struct SgdScalars { float alpha, beta, wd; };
 
 // ---------------------------------------------------------------------------
-// LDS view of one staged search table.
+// LDS map (64 KB per workgroup).  The bucket table is indexed by the upper half
+// of a binary32 pattern: keys of x in [0, 1] are 0 .. 0x3F80 and keys of x in
+// [-1, -0] are 0x8000 .. 0xBF80, which leaves two holes.  The first hole hosts
+// the non-negative half of the second table (used for the state r >= 0), the
+// second one the two codebooks and threshold arrays.  Every 16-bit key, also
+// that of a NaN, stays inside the 64 KB.
 // ---------------------------------------------------------------------------
-struct QView {
-    const float* qmap;
-    const float* thr;
-    const unsigned char* lut;
-    uint32_t shift, width, kbase, L;
-};
+constexpr int kLdsBytes = 0x10000;
+constexpr int kLutHalf = 0x3F90;          // bytes staged per half: keys 0 .. 0x3F8F
+constexpr int kLdsNeg = 0x8000;           // keys of negative x
+constexpr int kLdsU = 0x3F90;             // second table, keys of x >= 0
+constexpr int kLdsQ1 = 0xC000;            // first table: codebook, then thresholds
+constexpr int kLdsT1 = 0xC400;
+constexpr int kLdsQ2 = 0xC800;            // second table
+constexpr int kLdsT2 = 0xCC00;
+static_assert(kLdsU + kLutHalf <= kLdsNeg && kLdsNeg + kLutHalf <= kLdsQ1 && kLdsT2 + 1024 <= kLdsBytes, "LDS map");
 
-__device__ __forceinline__ void stage_qtable(unsigned char* lds, const void* qtab, int tid)
+__device__ __forceinline__ void copy16(unsigned char* dst, const unsigned char* src, int bytes, int tid)
 {
-    const uint4* src = static_cast<const uint4*>(qtab);
-    uint4* dst = reinterpret_cast<uint4*>(lds);
-    for (int i = tid; i < kQTabBytes / 16; i += kWgThreads) dst[i] = src[i];
+    gcuint4* s4 = (gcuint4*)src;
+    v4u* d4 = reinterpret_cast<v4u*>(dst);
+    for (int i = tid; i < bytes / 16; i += kWgThreads) d4[i] = s4[i];
 }
 
-__device__ __forceinline__ QView make_view(const unsigned char* lds)
+// first table: both signs
+__device__ __forceinline__ void stage_first(unsigned char* lds, const void* qtab, int tid)
 {
-    const QTabHeader* h = reinterpret_cast<const QTabHeader*>(lds);
-    QView v;
-    v.qmap = reinterpret_cast<const float*>(lds + kOffQmap);
-    v.thr = reinterpret_cast<const float*>(lds + kOffThr);
-    v.lut = lds + kOffLut;
-    v.shift = __builtin_amdgcn_readfirstlane(h->shift);
-    v.width = __builtin_amdgcn_readfirstlane(h->width);
-    v.kbase = __builtin_amdgcn_readfirstlane(h->kbase);
-    v.L = __builtin_amdgcn_readfirstlane(h->L);
-    return v;
+    const unsigned char* blob = static_cast<const unsigned char*>(qtab);
+    copy16(lds, blob + kOffLut, kLutHalf, tid);
+    copy16(lds + kLdsNeg, blob + kOffLut + 0x8000, kLutHalf, tid);
+    copy16(lds + kLdsQ1, blob + kOffQmap, 2048, tid);
+}
+
+// second table: non-negative half only
+__device__ __forceinline__ void stage_second(unsigned char* lds, const void* qtab, int tid)
+{
+    const unsigned char* blob = static_cast<const unsigned char*>(qtab);
+    copy16(lds + kLdsU, blob + kOffLut, kLutHalf, tid);
+    copy16(lds + kLdsQ2, blob + kOffQmap, 2048, tid);
 }
 
 // Nearest code of x (Eq. quant2) by bucket lookup + one exact threshold compare.
-template <bool NONNEG>
-__device__ __forceinline__ uint32_t nearest_code(const QView& q, float x)
+// SECOND selects the second table, whose inputs are non-negative.
+template <bool SECOND>
+__device__ __forceinline__ uint32_t nearest_code(const unsigned char* lds, float x)
 {
     const uint32_t bits = __float_as_uint(x);
-    const uint32_t a = __builtin_amdgcn_ubfe(bits, q.shift, q.width);
-    int idx = (int)a - (int)q.kbase;
-    idx = min(max(idx, 0), (int)q.L - 1);
-    if (!NONNEG) idx += (bits >> 31) ? (int)q.L : 0;
-    const uint32_t c = q.lut[idx];
-    const float t = q.thr[c];
+    uint32_t c;
+    float t;
+    if (SECOND) {
+        c = lds[kLdsU + __builtin_amdgcn_ubfe(bits, 16, 15)];
+        t = *reinterpret_cast<const float*>(lds + kLdsT2 + 4 * c);
+    } else {
+        c = lds[bits >> 16];
+        t = *reinterpret_cast<const float*>(lds + kLdsT1 + 4 * c);
+    }
     return c + ((x >= t) ? 1u : 0u);
+}
+
+template <bool SECOND>
+__device__ __forceinline__ float dequant(const unsigned char* lds, uint32_t code, float N)
+{
+    return *reinterpret_cast<const float*>(lds + (SECOND ? kLdsQ2 : kLdsQ1) + 4 * code) * N;
 }
 
 // ---------------------------------------------------------------------------
@@ -128,21 +168,22 @@ __device__ __forceinline__ uint32_t group_max(uint32_t v, int lane)
     return v;
 }
 
-// Correctly rounded a / N for a block-uniform N.  `fast` says N is in
-// [2^-60, 2^60] and y = RN(1/N); then for every |a| <= N either the quotient is
-// computed exactly as RN(a/N) (|a| >= 2^-102, no underflow in the residuals), or
-// |a / N| < 2^-40, far below the smallest threshold, where any tiny value gives
-// the same code.
-__device__ __forceinline__ float div_by_block_max(float a, float N, float y, bool fast)
+// Correctly rounded a / N for a block-uniform N in [2^-60, 2^60] with
+// y = RN(1/N): for every |a| <= N either the quotient is exactly RN(a/N)
+// (|a| >= 2^-102, no underflow in the residuals), or |a / N| < 2^-40, far below
+// the smallest threshold, where any tiny value gives the same code.
+__device__ __forceinline__ float div_fast(float a, float N, float y)
 {
-    if (fast) {
-        float q = a * y;
-        float r = __builtin_fmaf(-q, N, a);
-        q = __builtin_fmaf(r, y, q);
-        r = __builtin_fmaf(-q, N, a);
-        q = __builtin_fmaf(r, y, q);
-        return q;
-    }
+    float q = a * y;
+    float r = __builtin_fmaf(-q, N, a);
+    q = __builtin_fmaf(r, y, q);
+    r = __builtin_fmaf(-q, N, a);
+    q = __builtin_fmaf(r, y, q);
+    return q;
+}
+
+__device__ __forceinline__ float div_any(float a, float N)
+{
     return (N == 0.0f) ? 0.0f : a / N;
 }
 
@@ -159,7 +200,8 @@ __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
 
 // ---------------------------------------------------------------------------
 // Per-lane row access.  cnt = number of valid elements (0..4) of this lane in
-// the row; FULL tiles have cnt == 4 everywhere.
+// the row; FULL tiles have cnt == 4 everywhere.  The bulk data is touched once
+// per step, so full-width accesses carry the non-temporal hint.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int lane_count(int64_t n, int64_t e0)
 {
@@ -167,10 +209,10 @@ __device__ __forceinline__ int lane_count(int64_t n, int64_t e0)
     return left >= 4 ? 4 : (left <= 0 ? 0 : (int)left);
 }
 
-__device__ __forceinline__ void load4f(const float* __restrict__ p, int cnt, float (&v)[4])
+__device__ __forceinline__ void load4f(gcfloat* p, int cnt, float (&v)[4])
 {
     if (cnt == 4) {
-        float4 t = *reinterpret_cast<const float4*>(p);
+        const v4f t = __builtin_nontemporal_load((gcfloat4*)p);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
     } else {
 #pragma unroll
@@ -178,10 +220,11 @@ __device__ __forceinline__ void load4f(const float* __restrict__ p, int cnt, flo
     }
 }
 
-__device__ __forceinline__ void store4f(float* __restrict__ p, int cnt, const float (&v)[4])
+__device__ __forceinline__ void store4f(gfloat* p, int cnt, const float (&v)[4])
 {
     if (cnt == 4) {
-        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+        const v4f t = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(t, (gfloat4*)p);
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -189,9 +232,9 @@ __device__ __forceinline__ void store4f(float* __restrict__ p, int cnt, const fl
     }
 }
 
-__device__ __forceinline__ uint32_t load4b(const uint8_t* __restrict__ p, int cnt)
+__device__ __forceinline__ uint32_t load4b(gcbyte* p, int cnt)
 {
-    if (cnt == 4) return *reinterpret_cast<const uint32_t*>(p);
+    if (cnt == 4) return __builtin_nontemporal_load((gcu32*)p);
     uint32_t v = 0;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -199,10 +242,10 @@ __device__ __forceinline__ uint32_t load4b(const uint8_t* __restrict__ p, int cn
     return v;
 }
 
-__device__ __forceinline__ void store4b(uint8_t* __restrict__ p, int cnt, uint32_t v)
+__device__ __forceinline__ void store4b(gbyte* p, int cnt, uint32_t v)
 {
     if (cnt == 4) {
-        *reinterpret_cast<uint32_t*>(p) = v;
+        __builtin_nontemporal_store(v, (gu32*)p);
     } else {
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -210,61 +253,92 @@ __device__ __forceinline__ void store4b(uint8_t* __restrict__ p, int cnt, uint32
     }
 }
 
+// A workgroup of 8 waves advances one tile of TILE = max(B, 2048) elements per
+// step; wave v owns rows v*RW .. v*RW+RW-1 of the tile (RW = 1, or 2 for
+// B = 4096).  For B >= 256 the WPB = B / (256 RW) waves of a block exchange
+// their row maxima through LDS; for B < 256 a row holds 256/B blocks whose
+// maxima are formed by groups of B/4 lanes.
 template <int B>
 struct Shape {
     static constexpr int TILE = (B > 2048) ? B : 2048;
-    static constexpr int ROWS = TILE / kRow;
-    static constexpr int RPB = (B >= kRow) ? B / kRow : 1;      // rows per block
-    static constexpr int BPR = (B >= kRow) ? 1 : kRow / B;      // blocks per row
-    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;      // lanes per block in a row
-    static constexpr int NBLK = ROWS / RPB;                     // block slots per lane
+    static constexpr int RW = TILE / (kWavesPerWg * kRow);
+    static constexpr int WPB = (B >= kRow) ? (B / kRow) / RW : 1;
+    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;
 };
 
-// Re-quantize the ROWS x 4 values of this lane (Eq. quant1, quant2) and store
-// codes and block maxima.  `val` holds the new state, `amax` the per-slot lane
-// maxima of |val| as bit patterns.
-template <int B, bool FULL, bool NONNEG>
-__device__ __forceinline__ void requantize_store(const QView& q, float (&val)[Shape<B>::ROWS][4],
-                                                 uint32_t (&amax)[Shape<B>::NBLK],
-                                                 uint8_t* __restrict__ codes, float* __restrict__ Nout,
-                                                 int64_t n, int64_t base, int lane)
+// LDS words used for the exchange of row maxima: [parity][state][wave].
+struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
+
+// Block maxima of one or two states from the per-wave maxima.  All waves of the
+// workgroup call this once per tile when WPB > 1 (it contains the barrier).
+// Alternating `parity` between consecutive tiles makes one barrier per tile
+// sufficient: a slot is rewritten two tiles later, after a barrier that every
+// reader of the old value has passed.
+template <int WPB, int NSTATE>
+__device__ __forceinline__ void block_max(Exchange* ex, int parity, int wave, int lane, uint32_t (&v)[NSTATE])
+{
+    if (WPB == 1) return;
+    if (lane == 0) {
+#pragma unroll
+        for (int s = 0; s < NSTATE; ++s) ex->part[parity][s][wave] = v[s];
+    }
+    __syncthreads();
+    const int g0 = wave & ~(WPB - 1);
+#pragma unroll
+    for (int s = 0; s < NSTATE; ++s) {
+        uint32_t m = 0;
+#pragma unroll
+        for (int k = 0; k < WPB; ++k) m = max(m, ex->part[parity][s][g0 + k]);
+        v[s] = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
+    }
+}
+
+// Quantize the RW x 4 values of this lane (Eq. quant1, quant2) against the block
+// maximum `nbits` (bit pattern of N) and store the codes.
+template <int B, bool FULL, bool SECOND>
+__device__ __forceinline__ void requantize_rows(const unsigned char* lds, float (&val)[Shape<B>::RW][4],
+                                                uint32_t nbits, gbyte* codes, gfloat* Nout,
+                                                int64_t n, int64_t row0, int wave, int lane)
 {
     using S = Shape<B>;
+    const BlockNorm bn = make_norm(nbits);
+    if (B >= kRow) {
+        if ((wave & (S::WPB - 1)) == 0 && lane == 0 && (FULL || row0 < n)) Nout[row0 / B] = bn.N;
+    } else {
+        const int64_t e0 = row0 + lane * 4;
+        if ((lane % S::GROUP) == 0 && (FULL || e0 < n)) Nout[e0 / B] = bn.N;
+    }
+    // one wave-uniform decision keeps the common path straight-line
+    const bool all_fast = (S::GROUP == 64) ? bn.fast : (__builtin_amdgcn_ballot_w64(!bn.fast) == 0);
+    if (all_fast) {
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) {
-        const uint32_t nbits = group_max<S::GROUP>(amax[s], lane);
-        const BlockNorm bn = make_norm(nbits);
-        const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
-        // block index and writer lane
-        if (B >= kRow) {
-            if ((FULL || row0 < n) && lane == 0) Nout[row0 / B] = bn.N;
-        } else {
-            const int64_t e0 = row0 + lane * 4;
-            if ((FULL || e0 < n) && (lane % S::GROUP) == 0) Nout[e0 / B] = bn.N;
-        }
-#pragma unroll
-        for (int rr = 0; rr < S::RPB; ++rr) {
-            const int r = s * S::RPB + rr;
-            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        for (int i = 0; i < S::RW; ++i) {
+            const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
             const int cnt = FULL ? 4 : lane_count(n, e0);
-            if (!FULL && cnt == 0) continue;
             uint32_t packed = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float x = div_by_block_max(val[r][j], bn.N, bn.y, bn.fast);
-                packed |= nearest_code<NONNEG>(q, x) << (8 * j);
-            }
-            store4b(codes + e0, cnt, packed);
+            for (int j = 0; j < 4; ++j)
+                packed |= nearest_code<SECOND>(lds, div_fast(val[i][j], bn.N, bn.y)) << (8 * j);
+            if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < S::RW; ++i) {
+            const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+            const int cnt = FULL ? 4 : lane_count(n, e0);
+            uint32_t packed = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                packed |= nearest_code<SECOND>(lds, div_any(val[i][j], bn.N)) << (8 * j);
+            if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
         }
     }
 }
 
-// Old block maximum for row r of the tile (uniform for B >= 256, per lane group below).
+// Old block maximum of this wave's rows (uniform for B >= 256, per lane group below).
 template <int B, bool FULL>
-__device__ __forceinline__ float load_block_max(const float* __restrict__ N, int64_t n, int64_t base,
-                                                int r, int lane)
+__device__ __forceinline__ float load_block_max(gcfloat* N, int64_t n, int64_t row0, int lane)
 {
-    const int64_t row0 = base + (int64_t)r * kRow;
     if (B >= kRow) {
         if (!FULL && row0 >= n) return 0.0f;
         return N[row0 / B];
@@ -277,11 +351,12 @@ __device__ __forceinline__ float load_block_max(const float* __restrict__ N, int
 // ---------------------------------------------------------------------------
 // Element arithmetic (one statement = one rounded binary32 operation).
 // ---------------------------------------------------------------------------
+template <int WD>
 __device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, float g, float m_prev,
                                              float r_prev, float& m_out, float& r_out)
 {
     float wv = w;
-    if (s.coupled_wd) {
+    if (WD == 1) {
         float t0 = s.wd * wv;
         g = g + t0;
     }
@@ -297,7 +372,7 @@ __device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, flo
     float d = rs + s.eps;
     float u = m / d;
     float t6 = s.alpha_t * u;
-    if (s.decoupled_wd) {
+    if (WD == 2) {
         float t7 = s.alpha_wd * wv;
         wv = wv - t7;
     }
@@ -306,10 +381,11 @@ __device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, flo
     r_out = r;
 }
 
+template <bool WD>
 __device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float g, float m_prev, float& m_out)
 {
     float wv = w;
-    if (s.wd != 0.0f) {
+    if (WD) {
         float t0 = s.wd * wv;
         g = g + t0;
     }
@@ -321,177 +397,190 @@ __device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float
 }
 
 // ---------------------------------------------------------------------------
-// Tiles.
+// Tiles.  Every function below is entered by all 8 waves of the workgroup.
 // ---------------------------------------------------------------------------
-template <int B, bool FULL>
-__device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, const QView& qs, const QView& qu,
-                                           const AdamScalars& sc, int lane)
+template <int B, bool FULL, int WD>
+__device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, const unsigned char* lds,
+                                           Exchange* ex, int parity, const AdamScalars& sc, int wave, int lane)
 {
     using S = Shape<B>;
-    const int64_t base = tile * S::TILE;
     const int64_t n = d.n;
-    float wv[S::ROWS][4], gv[S::ROWS][4];
-    uint32_t mq[S::ROWS], rq[S::ROWS];
-    float Nm_old[S::ROWS], Nr_old[S::ROWS];
+    const int64_t row0 = tile * S::TILE + (int64_t)wave * S::RW * kRow;
+    gfloat* w = (gfloat*)d.w;
+    gcfloat* g = (gcfloat*)d.g;
+    gbyte* m_q = (gbyte*)d.m_q;
+    gbyte* r_q = (gbyte*)d.r_q;
+    float wv[S::RW][4], gv[S::RW][4];
+    uint32_t mq[S::RW], rq[S::RW];
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
-        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+    for (int i = 0; i < S::RW; ++i) {
+        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(d.w + e0, cnt, wv[r]);
-            load4f(d.g + e0, cnt, gv[r]);
-            mq[r] = load4b(d.m_q + e0, cnt);
-            rq[r] = load4b(d.r_q + e0, cnt);
+            load4f(w + e0, cnt, wv[i]);
+            load4f(g + e0, cnt, gv[i]);
+            mq[i] = load4b(m_q + e0, cnt);
+            rq[i] = load4b(r_q + e0, cnt);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
-            mq[r] = 0; rq[r] = 0;
+            for (int j = 0; j < 4; ++j) { wv[i][j] = 0.0f; gv[i][j] = 0.0f; }
+            mq[i] = 0; rq[i] = 0;
         }
-        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
-        Nr_old[r] = load_block_max<B, FULL>(d.N_r, n, base, r, lane);
     }
-    uint32_t amax_m[S::NBLK], amax_r[S::NBLK];
-#pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) { amax_m[s] = 0; amax_r[s] = 0; }
+    const float Nm_old = load_block_max<B, FULL>((gcfloat*)d.N_m, n, row0, lane);
+    const float Nr_old = load_block_max<B, FULL>((gcfloat*)d.N_r, n, row0, lane);
+    uint32_t amax[2] = {0u, 0u};
     // after this loop gv holds the new m and wv is reused for the new r
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
-        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+    for (int i = 0; i < S::RW; ++i) {
+        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         float rnew[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m_prev = qs.qmap[(mq[r] >> (8 * j)) & 0xff] * Nm_old[r];
-            const float r_prev = qu.qmap[(rq[r] >> (8 * j)) & 0xff] * Nr_old[r];
+            const float m_prev = dequant<false>(lds, (mq[i] >> (8 * j)) & 0xff, Nm_old);
+            const float r_prev = dequant<true>(lds, (rq[i] >> (8 * j)) & 0xff, Nr_old);
             float m_new, r_new;
-            adam_element(sc, wv[r][j], gv[r][j], m_prev, r_prev, m_new, r_new);
+            adam_element<WD>(sc, wv[i][j], gv[i][j], m_prev, r_prev, m_new, r_new);
             if (!FULL && j >= cnt) { m_new = 0.0f; r_new = 0.0f; }
-            gv[r][j] = m_new;
+            gv[i][j] = m_new;
             rnew[j] = r_new;
-            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
-            amax_r[r / S::RPB] = max(amax_r[r / S::RPB], __float_as_uint(r_new));
+            amax[0] = max(amax[0], __float_as_uint(m_new) & 0x7fffffffu);
+            amax[1] = max(amax[1], __float_as_uint(r_new));
         }
-        if (FULL || cnt > 0) store4f(d.w + e0, cnt, wv[r]);
+        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[i]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wv[r][j] = rnew[j];
+        for (int j = 0; j < 4; ++j) wv[i][j] = rnew[j];
     }
-    requantize_store<B, FULL, false>(qs, gv, amax_m, d.m_q, d.N_m, n, base, lane);
-    requantize_store<B, FULL, true>(qu, wv, amax_r, d.r_q, d.N_r, n, base, lane);
+    amax[0] = group_max<S::GROUP>(amax[0], lane);
+    amax[1] = group_max<S::GROUP>(amax[1], lane);
+    block_max<S::WPB, 2>(ex, parity, wave, lane, amax);
+    requantize_rows<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, row0, wave, lane);
+    requantize_rows<B, FULL, true>(lds, wv, amax[1], r_q, (gfloat*)d.N_r, n, row0, wave, lane);
 }
 
-template <int B, bool FULL>
-__device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, const QView& qs,
-                                          const SgdScalars& sc, int lane)
+template <int B, bool FULL, bool WD>
+__device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, const unsigned char* lds,
+                                          Exchange* ex, int parity, const SgdScalars& sc, int wave, int lane)
 {
     using S = Shape<B>;
-    const int64_t base = tile * S::TILE;
     const int64_t n = d.n;
-    float wv[S::ROWS][4], gv[S::ROWS][4];
-    uint32_t mq[S::ROWS];
-    float Nm_old[S::ROWS];
+    const int64_t row0 = tile * S::TILE + (int64_t)wave * S::RW * kRow;
+    gfloat* w = (gfloat*)d.w;
+    gcfloat* g = (gcfloat*)d.g;
+    gbyte* m_q = (gbyte*)d.m_q;
+    float wv[S::RW][4], gv[S::RW][4];
+    uint32_t mq[S::RW];
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
-        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+    for (int i = 0; i < S::RW; ++i) {
+        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(d.w + e0, cnt, wv[r]);
-            load4f(d.g + e0, cnt, gv[r]);
-            mq[r] = load4b(d.m_q + e0, cnt);
+            load4f(w + e0, cnt, wv[i]);
+            load4f(g + e0, cnt, gv[i]);
+            mq[i] = load4b(m_q + e0, cnt);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
-            mq[r] = 0;
+            for (int j = 0; j < 4; ++j) { wv[i][j] = 0.0f; gv[i][j] = 0.0f; }
+            mq[i] = 0;
         }
-        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
     }
-    uint32_t amax_m[S::NBLK];
+    const float Nm_old = load_block_max<B, FULL>((gcfloat*)d.N_m, n, row0, lane);
+    uint32_t amax[1] = {0u};
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) amax_m[s] = 0;
-#pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
-        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+    for (int i = 0; i < S::RW; ++i) {
+        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m_prev = qs.qmap[(mq[r] >> (8 * j)) & 0xff] * Nm_old[r];
+            const float m_prev = dequant<false>(lds, (mq[i] >> (8 * j)) & 0xff, Nm_old);
             float m_new;
-            sgd_element(sc, wv[r][j], gv[r][j], m_prev, m_new);
+            sgd_element<WD>(sc, wv[i][j], gv[i][j], m_prev, m_new);
             if (!FULL && j >= cnt) m_new = 0.0f;
-            gv[r][j] = m_new;
-            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
+            gv[i][j] = m_new;
+            amax[0] = max(amax[0], __float_as_uint(m_new) & 0x7fffffffu);
         }
-        if (FULL || cnt > 0) store4f(d.w + e0, cnt, wv[r]);
+        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[i]);
     }
-    requantize_store<B, FULL, false>(qs, gv, amax_m, d.m_q, d.N_m, n, base, lane);
+    amax[0] = group_max<S::GROUP>(amax[0], lane);
+    block_max<S::WPB, 1>(ex, parity, wave, lane, amax);
+    requantize_rows<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, row0, wave, lane);
 }
 
-// Tensors that keep 32-bit states: same formulas, no quantization.  Processed
-// in the same 2048-element wave tiles.
+// Tensors that keep 32-bit states: same formulas, no quantization, no barrier.
 template <bool ADAM>
 __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t tile, int tile_elems,
-                                         const AdamScalars& as, const SgdScalars& ss, int lane)
+                                         const AdamScalars& as, const SgdScalars& ss, int wave, int lane)
 {
-    const int64_t base = tile * tile_elems;
     const int64_t n = d.n;
-    for (int r = 0; r < tile_elems / kRow; ++r) {
-        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+    const int rw = tile_elems / (kWavesPerWg * kRow);
+    const int64_t row0 = tile * tile_elems + (int64_t)wave * rw * kRow;
+    gfloat* w = (gfloat*)d.w;
+    gcfloat* g = (gcfloat*)d.g;
+    gfloat* m = (gfloat*)d.m_f32;
+    gfloat* rr = (gfloat*)d.r_f32;
+    for (int i = 0; i < rw; ++i) {
+        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
         const int cnt = lane_count(n, e0);
         if (cnt == 0) continue;
         float wv[4], gv[4], mv[4], rv[4] = {0.f, 0.f, 0.f, 0.f};
-        load4f(d.w + e0, cnt, wv);
-        load4f(d.g + e0, cnt, gv);
-        load4f(d.m_f32 + e0, cnt, mv);
-        if (ADAM) load4f(d.r_f32 + e0, cnt, rv);
+        load4f(w + e0, cnt, wv);
+        load4f(g + e0, cnt, gv);
+        load4f(m + e0, cnt, mv);
+        if (ADAM) load4f(rr + e0, cnt, rv);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (ADAM) adam_element(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
-            else sgd_element(ss, wv[j], gv[j], mv[j], mv[j]);
+            if (ADAM) {
+                if (as.wd_mode == 1) adam_element<1>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                else if (as.wd_mode == 2) adam_element<2>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                else adam_element<0>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+            } else {
+                if (ss.wd != 0.0f) sgd_element<true>(ss, wv[j], gv[j], mv[j], mv[j]);
+                else sgd_element<false>(ss, wv[j], gv[j], mv[j], mv[j]);
+            }
         }
-        store4f(d.w + e0, cnt, wv);
-        store4f(d.m_f32 + e0, cnt, mv);
-        if (ADAM) store4f(d.r_f32 + e0, cnt, rv);
+        store4f(w + e0, cnt, wv);
+        store4f(m + e0, cnt, mv);
+        if (ADAM) store4f(rr + e0, cnt, rv);
     }
 }
 
 template <int B, bool FULL>
-__device__ __forceinline__ void quant_tile(const float* __restrict__ T, uint8_t* __restrict__ TQ,
-                                           float* __restrict__ N, int64_t n, int64_t tile, const QView& q, int lane)
+__device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int64_t n, int64_t tile,
+                                           const unsigned char* lds, Exchange* ex, int parity, int wave, int lane)
 {
     using S = Shape<B>;
-    const int64_t base = tile * S::TILE;
-    float v[S::ROWS][4];
-    uint32_t amax[S::NBLK];
+    const int64_t row0 = tile * S::TILE + (int64_t)wave * S::RW * kRow;
+    float v[S::RW][4];
+    uint32_t amax[1] = {0u};
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) amax[s] = 0;
-#pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
-        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+    for (int i = 0; i < S::RW; ++i) {
+        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(T + e0, cnt, v[r]);
+            load4f(T + e0, cnt, v[i]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
+            for (int j = 0; j < 4; ++j) v[i][j] = 0.0f;
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            amax[r / S::RPB] = max(amax[r / S::RPB], __float_as_uint(v[r][j]) & 0x7fffffffu);
+        for (int j = 0; j < 4; ++j) amax[0] = max(amax[0], __float_as_uint(v[i][j]) & 0x7fffffffu);
     }
-    requantize_store<B, FULL, false>(q, v, amax, TQ, N, n, base, lane);
+    amax[0] = group_max<S::GROUP>(amax[0], lane);
+    block_max<S::WPB, 1>(ex, parity, wave, lane, amax);
+    requantize_rows<B, FULL, false>(lds, v, amax[0], TQ, N, n, row0, wave, lane);
 }
 
 // ---------------------------------------------------------------------------
 // Persistent tile walk.  Workgroup ids are dealt round-robin to the 8 XCDs, so
 // ids are re-numbered to give every XCD one contiguous run of tiles per pass.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ int64_t first_tile(int& stride)
+__device__ __forceinline__ int64_t first_tile()
 {
     const int G = gridDim.x;
     int vb = blockIdx.x;
     if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
-    stride = G * kWavesPerWg;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    return (int64_t)vb * kWavesPerWg + wave;
+    return vb;
 }
 
 struct StepArgs {
@@ -503,38 +592,87 @@ struct StepArgs {
     const void* qtab_u;
 };
 
+// Tile -> (tensor descriptor, tile index inside the tensor).  The tables are read
+// through the constant address space with wave-uniform indices, i.e. by scalar
+// loads into SGPRs.
+#define Q8_CONSTANT __attribute__((address_space(4)))
 __device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t t, int64_t& tile_in_tensor)
 {
     if (a.tiles) {
-        const TileRef ref = a.tiles[t];
-        const int ti = __builtin_amdgcn_readfirstlane(ref.tensor);
-        tile_in_tensor = __builtin_amdgcn_readfirstlane(ref.tile);
-        return a.descs[ti];
+        Q8_CONSTANT const int32_t* ref = (Q8_CONSTANT const int32_t*)a.tiles + 2 * t;
+        const int ti = ref[0];
+        tile_in_tensor = ref[1];
+        Q8_CONSTANT const uint64_t* f = (Q8_CONSTANT const uint64_t*)(a.descs + ti);
+        TensorDesc d;
+        d.w = (float*)f[0];
+        d.g = (const float*)f[1];
+        d.m_q = (uint8_t*)f[2];
+        d.r_q = (uint8_t*)f[3];
+        d.N_m = (float*)f[4];
+        d.N_r = (float*)f[5];
+        d.m_f32 = (float*)f[6];
+        d.r_f32 = (float*)f[7];
+        d.n = (int64_t)f[8];
+        return d;
     }
     tile_in_tensor = t;
     return a.single;
+}
+static_assert(sizeof(TensorDesc) == 72 && sizeof(TileRef) == 8, "descriptor layout");
+
+struct Lds {
+    unsigned char tab[kLdsBytes];
+    Exchange ex;
+};
+
+template <int B, int WD>
+__device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars& sc, Lds* lds)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    SgdScalars none{};
+    int parity = 0;
+    for (int64_t t = first_tile(); t < a.ntiles; t += gridDim.x, parity ^= 1) {
+        int64_t tt;
+        const TensorDesc d = resolve(a, t, tt);
+        if (d.m_f32) {
+            f32_tile<true>(d, tt, Shape<B>::TILE, sc, none, wave, lane);
+        } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
+            adam8_tile<B, true, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
+        } else {
+            adam8_tile<B, false, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
+        }
+    }
 }
 
 template <int B>
 __global__ __launch_bounds__(kWgThreads) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kQTabBytes];
-    stage_qtable(lds, a.qtab_s, threadIdx.x);
-    stage_qtable(lds + kQTabBytes, a.qtab_u, threadIdx.x);
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    stage_first(lds.tab, a.qtab_s, threadIdx.x);
+    stage_second(lds.tab, a.qtab_u, threadIdx.x);
     __syncthreads();
-    const QView qs = make_view(lds), qu = make_view(lds + kQTabBytes);
+    if (sc.wd_mode == 0) adam8_walk<B, 0>(a, sc, &lds);
+    else if (sc.wd_mode == 1) adam8_walk<B, 1>(a, sc, &lds);
+    else adam8_walk<B, 2>(a, sc, &lds);
+}
+
+template <int B, bool WD>
+__device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& sc, Lds* lds)
+{
     const int lane = threadIdx.x & 63;
-    int stride;
-    SgdScalars none{};
-    for (int64_t t = first_tile(stride); t < a.ntiles; t += stride) {
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    AdamScalars none{};
+    int parity = 0;
+    for (int64_t t = first_tile(); t < a.ntiles; t += gridDim.x, parity ^= 1) {
         int64_t tt;
         const TensorDesc d = resolve(a, t, tt);
         if (d.m_f32) {
-            f32_tile<true>(d, tt, Shape<B>::TILE, sc, none, lane);
+            f32_tile<false>(d, tt, Shape<B>::TILE, none, sc, wave, lane);
         } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
-            adam8_tile<B, true>(d, tt, qs, qu, sc, lane);
+            sgd8_tile<B, true, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
         } else {
-            adam8_tile<B, false>(d, tt, qs, qu, sc, lane);
+            sgd8_tile<B, false, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
         }
     }
 }
@@ -542,55 +680,45 @@ __global__ __launch_bounds__(kWgThreads) void adam8_kernel(StepArgs a, AdamScala
 template <int B>
 __global__ __launch_bounds__(kWgThreads) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kQTabBytes];
-    stage_qtable(lds, a.qtab_s, threadIdx.x);
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    stage_first(lds.tab, a.qtab_s, threadIdx.x);
     __syncthreads();
-    const QView qs = make_view(lds);
-    const int lane = threadIdx.x & 63;
-    int stride;
-    AdamScalars none{};
-    for (int64_t t = first_tile(stride); t < a.ntiles; t += stride) {
-        int64_t tt;
-        const TensorDesc d = resolve(a, t, tt);
-        if (d.m_f32) {
-            f32_tile<false>(d, tt, Shape<B>::TILE, none, sc, lane);
-        } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
-            sgd8_tile<B, true>(d, tt, qs, sc, lane);
-        } else {
-            sgd8_tile<B, false>(d, tt, qs, sc, lane);
-        }
-    }
+    if (sc.wd != 0.0f) sgd8_walk<B, true>(a, sc, &lds);
+    else sgd8_walk<B, false>(a, sc, &lds);
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads) void quantize_kernel(const void* qtab, const float* __restrict__ T,
-                                                              uint8_t* __restrict__ TQ, float* __restrict__ N,
-                                                              int64_t n, int64_t ntiles)
+__global__ __launch_bounds__(kWgThreads) void quantize_kernel(const void* qtab, const float* T, uint8_t* TQ,
+                                                              float* N, int64_t n, int64_t ntiles)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds[kQTabBytes];
-    stage_qtable(lds, qtab, threadIdx.x);
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    stage_first(lds.tab, qtab, threadIdx.x);
     __syncthreads();
-    const QView q = make_view(lds);
     const int lane = threadIdx.x & 63;
-    int stride;
-    for (int64_t t = first_tile(stride); t < ntiles; t += stride) {
-        if ((t + 1) * Shape<B>::TILE <= n) quant_tile<B, true>(T, TQ, N, n, t, q, lane);
-        else quant_tile<B, false>(T, TQ, N, n, t, q, lane);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    int parity = 0;
+    for (int64_t t = first_tile(); t < ntiles; t += gridDim.x, parity ^= 1) {
+        if ((t + 1) * Shape<B>::TILE <= n)
+            quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, &lds.ex, parity, wave, lane);
+        else
+            quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, &lds.ex, parity, wave, lane);
     }
 }
 
 // Eq. quant3.  One thread handles 4 consecutive elements per step; the block
 // index of an element is (index >> log2 B).
-__global__ __launch_bounds__(kWgThreads) void dequantize_kernel(const void* qtab, const uint8_t* __restrict__ TQ,
-                                                                const float* __restrict__ N, int64_t n, int log2B,
-                                                                float* __restrict__ TD)
+__global__ __launch_bounds__(256) void dequantize_kernel(const void* qtab, const uint8_t* TQ_, const float* N_,
+                                                         int64_t n, int log2B, float* TD_)
 {
     __shared__ float qmap[256];
-    qmap[threadIdx.x] = reinterpret_cast<const float*>(static_cast<const unsigned char*>(qtab) + kOffQmap)[threadIdx.x];
+    qmap[threadIdx.x] = ((gcfloat*)(static_cast<const unsigned char*>(qtab) + kOffQmap))[threadIdx.x];
     __syncthreads();
+    gcbyte* TQ = (gcbyte*)TQ_;
+    gcfloat* N = (gcfloat*)N_;
+    gfloat* TD = (gfloat*)TD_;
     const int64_t nvec = (n + 3) >> 2;
-    const int64_t stride = (int64_t)gridDim.x * kWgThreads;
-    for (int64_t v = (int64_t)blockIdx.x * kWgThreads + threadIdx.x; v < nvec; v += stride) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t v = (int64_t)blockIdx.x * 256 + threadIdx.x; v < nvec; v += stride) {
         const int64_t e0 = v * 4;
         const int cnt = lane_count(n, e0);
         const uint32_t c = load4b(TQ + e0, cnt);
@@ -630,7 +758,7 @@ q8_status device_info(DeviceInfo& out)
 }
 
 // Persistent grid: enough workgroups to fill every CU to the kernel's
-// occupancy, never more than there are 4-tile groups of work.
+// occupancy, never more than there are tiles.
 // `per_cu` caches the occupancy query of one kernel (0 = not asked yet).
 template <typename K>
 q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid)
@@ -644,7 +772,7 @@ q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid)
             return Q8_ELAUNCH;
         per_cu = v;
     }
-    int64_t want = (ntiles + kWavesPerWg - 1) / kWavesPerWg;
+    int64_t want = ntiles;                 // one workgroup step per tile
     int64_t cap = (int64_t)di.cus * per_cu;
     grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
@@ -696,8 +824,7 @@ q8_status make_adam_scalars(float alpha, float beta1, float beta2, float eps, fl
         s.isbc2 = (float)(1.0 / sqrt(bc2));
     }
     s.alpha_wd = alpha * wd;
-    s.coupled_wd = (wd != 0.0f) && !(flags & Q8_FLAG_DECOUPLED_WD);
-    s.decoupled_wd = (wd != 0.0f) && (flags & Q8_FLAG_DECOUPLED_WD);
+    s.wd_mode = (wd == 0.0f) ? 0 : ((flags & Q8_FLAG_DECOUPLED_WD) ? 2 : 1);
     return Q8_OK;
 }
 
@@ -770,10 +897,10 @@ extern "C" q8_status q8_dequantize_blockwise(const void* qtable, const uint8_t* 
     q8_status st = device_info(di);
     if (st != Q8_OK) return st;
     const int64_t nvec = (n + 3) / 4;
-    int64_t want = (nvec + kWgThreads - 1) / kWgThreads;
+    int64_t want = (nvec + 255) / 256;
     int64_t cap = (int64_t)di.cus * 8;
     const int grid = (int)(want < cap ? want : cap);
-    hipLaunchKernelGGL(dequantize_kernel, dim3(grid), dim3(kWgThreads), 0, static_cast<hipStream_t>(stream),
+    hipLaunchKernelGGL(dequantize_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
                        qtable, TQ, N, n, ilog2(B), TD);
     return launch_status();
 }

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libq8opt.so")
+LIB_PATH = os.environ.get("Q8OPT_LIB", os.path.join(_HERE, "libq8opt.so"))   # override: another build of the library
 
 FLAG_BIAS_CORRECTION = 1
 FLAG_DECOUPLED_WD = 2
