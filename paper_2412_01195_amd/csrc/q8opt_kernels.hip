@@ -8,8 +8,16 @@
 // 128-bit load/store per lane and every code access one coalesced 32-bit one.
 // New states stay in registers between the update and the re-quantization; the
 // block absmax needs only cross-lane DPP steps inside the wave (no barrier, no
-// LDS traffic).  Workgroups of 8 waves are persistent: they stage the search
-// tables into 64 KB of LDS once and then walk over tiles with a grid stride.
+// LDS traffic), and per-block work (reduction, reciprocal) is amortised over 32
+// elements per lane.
+//
+// Scheduling: workgroups of 8 waves are persistent.  They stage the search tables
+// into 64 KB of LDS once and then draw "jobs" of 8 consecutive tiles (one per
+// wave) from an atomic counter in device memory.  Handing tiles out in address
+// order to whichever workgroup is free keeps the set of addresses in flight one
+// dense, slowly advancing window over each stream, which is what the HBM
+// controllers reward; a static grid-stride or chunked assignment measured 10-15 %
+// slower on the same access pattern.
 //
 // Nearest-code search (Eq. quant2): the upper 16 bits of the binary32 pattern of
 // x = m / N index a byte table in LDS that holds the code at the lower end of that
@@ -24,6 +32,8 @@
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
+
+#include <atomic>
 
 #include "q8opt.h"
 #include "q8opt_internal.h"
@@ -253,92 +263,71 @@ __device__ __forceinline__ void store4b(gbyte* p, int cnt, uint32_t v)
     }
 }
 
-// A workgroup of 8 waves advances one tile of TILE = max(B, 2048) elements per
-// step; wave v owns rows v*RW .. v*RW+RW-1 of the tile (RW = 1, or 2 for
-// B = 4096).  For B >= 256 the WPB = B / (256 RW) waves of a block exchange
-// their row maxima through LDS; for B < 256 a row holds 256/B blocks whose
-// maxima are formed by groups of B/4 lanes.
 template <int B>
 struct Shape {
     static constexpr int TILE = (B > 2048) ? B : 2048;
-    static constexpr int RW = TILE / (kWavesPerWg * kRow);
-    static constexpr int WPB = (B >= kRow) ? (B / kRow) / RW : 1;
-    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;
+    static constexpr int ROWS = TILE / kRow;
+    static constexpr int RPB = (B >= kRow) ? B / kRow : 1;      // rows per block
+    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;      // lanes per block in a row
+    static constexpr int NBLK = ROWS / RPB;                     // block slots per lane
 };
 
-// LDS words used for the exchange of row maxima: [parity][state][wave].
-struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
-
-// Block maxima of one or two states from the per-wave maxima.  All waves of the
-// workgroup call this once per tile when WPB > 1 (it contains the barrier).
-// Alternating `parity` between consecutive tiles makes one barrier per tile
-// sufficient: a slot is rewritten two tiles later, after a barrier that every
-// reader of the old value has passed.
-template <int WPB, int NSTATE>
-__device__ __forceinline__ void block_max(Exchange* ex, int parity, int wave, int lane, uint32_t (&v)[NSTATE])
-{
-    if (WPB == 1) return;
-    if (lane == 0) {
-#pragma unroll
-        for (int s = 0; s < NSTATE; ++s) ex->part[parity][s][wave] = v[s];
-    }
-    __syncthreads();
-    const int g0 = wave & ~(WPB - 1);
-#pragma unroll
-    for (int s = 0; s < NSTATE; ++s) {
-        uint32_t m = 0;
-#pragma unroll
-        for (int k = 0; k < WPB; ++k) m = max(m, ex->part[parity][s][g0 + k]);
-        v[s] = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
-    }
-}
-
-// Quantize the RW x 4 values of this lane (Eq. quant1, quant2) against the block
-// maximum `nbits` (bit pattern of N) and store the codes.
+// Re-quantize the ROWS x 4 values of this lane (Eq. quant1, quant2) and store
+// codes and block maxima.  `val` holds the new state, `amax` the per-slot lane
+// maxima of |val| as bit patterns.
 template <int B, bool FULL, bool SECOND>
-__device__ __forceinline__ void requantize_rows(const unsigned char* lds, float (&val)[Shape<B>::RW][4],
-                                                uint32_t nbits, gbyte* codes, gfloat* Nout,
-                                                int64_t n, int64_t row0, int wave, int lane)
+__device__ __forceinline__ void requantize_store(const unsigned char* lds, float (&val)[Shape<B>::ROWS][4],
+                                                 uint32_t (&amax)[Shape<B>::NBLK],
+                                                 gbyte* codes, gfloat* Nout,
+                                                 int64_t n, int64_t base, int lane)
 {
     using S = Shape<B>;
-    const BlockNorm bn = make_norm(nbits);
-    if (B >= kRow) {
-        if ((wave & (S::WPB - 1)) == 0 && lane == 0 && (FULL || row0 < n)) Nout[row0 / B] = bn.N;
-    } else {
-        const int64_t e0 = row0 + lane * 4;
-        if ((lane % S::GROUP) == 0 && (FULL || e0 < n)) Nout[e0 / B] = bn.N;
-    }
-    // one wave-uniform decision keeps the common path straight-line
-    const bool all_fast = (S::GROUP == 64) ? bn.fast : (__builtin_amdgcn_ballot_w64(!bn.fast) == 0);
-    if (all_fast) {
 #pragma unroll
-        for (int i = 0; i < S::RW; ++i) {
-            const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
-            const int cnt = FULL ? 4 : lane_count(n, e0);
-            uint32_t packed = 0;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                packed |= nearest_code<SECOND>(lds, div_fast(val[i][j], bn.N, bn.y)) << (8 * j);
-            if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+    for (int s = 0; s < S::NBLK; ++s) {
+        const uint32_t nbits = group_max<S::GROUP>(amax[s], lane);
+        const BlockNorm bn = make_norm(nbits);
+        const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
+        if (B >= kRow) {
+            if ((FULL || row0 < n) && lane == 0) Nout[row0 / B] = bn.N;
+        } else {
+            const int64_t e0 = row0 + lane * 4;
+            if ((FULL || e0 < n) && (lane % S::GROUP) == 0) Nout[e0 / B] = bn.N;
         }
-    } else {
+        // one wave-uniform decision per block slot keeps the common path straight-line
+        const bool all_fast = (S::GROUP == 64) ? bn.fast : (__builtin_amdgcn_ballot_w64(!bn.fast) == 0);
+        if (all_fast) {
 #pragma unroll
-        for (int i = 0; i < S::RW; ++i) {
-            const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
-            const int cnt = FULL ? 4 : lane_count(n, e0);
-            uint32_t packed = 0;
+            for (int rr = 0; rr < S::RPB; ++rr) {
+                const int r = s * S::RPB + rr;
+                const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+                const int cnt = FULL ? 4 : lane_count(n, e0);
+                uint32_t packed = 0;
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                packed |= nearest_code<SECOND>(lds, div_any(val[i][j], bn.N)) << (8 * j);
-            if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+                for (int j = 0; j < 4; ++j)
+                    packed |= nearest_code<SECOND>(lds, div_fast(val[r][j], bn.N, bn.y)) << (8 * j);
+                if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+            }
+        } else {
+#pragma unroll
+            for (int rr = 0; rr < S::RPB; ++rr) {
+                const int r = s * S::RPB + rr;
+                const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+                const int cnt = FULL ? 4 : lane_count(n, e0);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    packed |= nearest_code<SECOND>(lds, div_any(val[r][j], bn.N)) << (8 * j);
+                if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+            }
         }
     }
 }
 
-// Old block maximum of this wave's rows (uniform for B >= 256, per lane group below).
+// Old block maximum for row r of the tile (uniform for B >= 256, per lane group below).
 template <int B, bool FULL>
-__device__ __forceinline__ float load_block_max(gcfloat* N, int64_t n, int64_t row0, int lane)
+__device__ __forceinline__ float load_block_max(gcfloat* N, int64_t n, int64_t base, int r, int lane)
 {
+    const int64_t row0 = base + (int64_t)r * kRow;
     if (B >= kRow) {
         if (!FULL && row0 >= n) return 0.0f;
         return N[row0 / B];
@@ -397,130 +386,131 @@ __device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float
 }
 
 // ---------------------------------------------------------------------------
-// Tiles.  Every function below is entered by all 8 waves of the workgroup.
+// Tiles (one wave each).
 // ---------------------------------------------------------------------------
 template <int B, bool FULL, int WD>
 __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, const unsigned char* lds,
-                                           Exchange* ex, int parity, const AdamScalars& sc, int wave, int lane)
+                                           const AdamScalars& sc, int lane)
 {
     using S = Shape<B>;
+    const int64_t base = tile * S::TILE;
     const int64_t n = d.n;
-    const int64_t row0 = tile * S::TILE + (int64_t)wave * S::RW * kRow;
     gfloat* w = (gfloat*)d.w;
     gcfloat* g = (gcfloat*)d.g;
     gbyte* m_q = (gbyte*)d.m_q;
     gbyte* r_q = (gbyte*)d.r_q;
-    float wv[S::RW][4], gv[S::RW][4];
-    uint32_t mq[S::RW], rq[S::RW];
+    float wv[S::ROWS][4], gv[S::ROWS][4];
+    uint32_t mq[S::ROWS], rq[S::ROWS];
+    float Nm_old[S::ROWS], Nr_old[S::ROWS];
 #pragma unroll
-    for (int i = 0; i < S::RW; ++i) {
-        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+    for (int r = 0; r < S::ROWS; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(w + e0, cnt, wv[i]);
-            load4f(g + e0, cnt, gv[i]);
-            mq[i] = load4b(m_q + e0, cnt);
-            rq[i] = load4b(r_q + e0, cnt);
+            load4f(w + e0, cnt, wv[r]);
+            load4f(g + e0, cnt, gv[r]);
+            mq[r] = load4b(m_q + e0, cnt);
+            rq[r] = load4b(r_q + e0, cnt);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { wv[i][j] = 0.0f; gv[i][j] = 0.0f; }
-            mq[i] = 0; rq[i] = 0;
+            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
+            mq[r] = 0; rq[r] = 0;
         }
+        Nm_old[r] = load_block_max<B, FULL>((gcfloat*)d.N_m, n, base, r, lane);
+        Nr_old[r] = load_block_max<B, FULL>((gcfloat*)d.N_r, n, base, r, lane);
     }
-    const float Nm_old = load_block_max<B, FULL>((gcfloat*)d.N_m, n, row0, lane);
-    const float Nr_old = load_block_max<B, FULL>((gcfloat*)d.N_r, n, row0, lane);
-    uint32_t amax[2] = {0u, 0u};
+    uint32_t amax_m[S::NBLK], amax_r[S::NBLK];
+#pragma unroll
+    for (int s = 0; s < S::NBLK; ++s) { amax_m[s] = 0; amax_r[s] = 0; }
     // after this loop gv holds the new m and wv is reused for the new r
 #pragma unroll
-    for (int i = 0; i < S::RW; ++i) {
-        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+    for (int r = 0; r < S::ROWS; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         float rnew[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m_prev = dequant<false>(lds, (mq[i] >> (8 * j)) & 0xff, Nm_old);
-            const float r_prev = dequant<true>(lds, (rq[i] >> (8 * j)) & 0xff, Nr_old);
+            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
+            const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[r]);
             float m_new, r_new;
-            adam_element<WD>(sc, wv[i][j], gv[i][j], m_prev, r_prev, m_new, r_new);
+            adam_element<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, m_new, r_new);
             if (!FULL && j >= cnt) { m_new = 0.0f; r_new = 0.0f; }
-            gv[i][j] = m_new;
+            gv[r][j] = m_new;
             rnew[j] = r_new;
-            amax[0] = max(amax[0], __float_as_uint(m_new) & 0x7fffffffu);
-            amax[1] = max(amax[1], __float_as_uint(r_new));
+            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
+            amax_r[r / S::RPB] = max(amax_r[r / S::RPB], __float_as_uint(r_new));
         }
-        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[i]);
+        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wv[i][j] = rnew[j];
+        for (int j = 0; j < 4; ++j) wv[r][j] = rnew[j];
     }
-    amax[0] = group_max<S::GROUP>(amax[0], lane);
-    amax[1] = group_max<S::GROUP>(amax[1], lane);
-    block_max<S::WPB, 2>(ex, parity, wave, lane, amax);
-    requantize_rows<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, row0, wave, lane);
-    requantize_rows<B, FULL, true>(lds, wv, amax[1], r_q, (gfloat*)d.N_r, n, row0, wave, lane);
+    requantize_store<B, FULL, false>(lds, gv, amax_m, m_q, (gfloat*)d.N_m, n, base, lane);
+    requantize_store<B, FULL, true>(lds, wv, amax_r, r_q, (gfloat*)d.N_r, n, base, lane);
 }
 
 template <int B, bool FULL, bool WD>
 __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, const unsigned char* lds,
-                                          Exchange* ex, int parity, const SgdScalars& sc, int wave, int lane)
+                                          const SgdScalars& sc, int lane)
 {
     using S = Shape<B>;
+    const int64_t base = tile * S::TILE;
     const int64_t n = d.n;
-    const int64_t row0 = tile * S::TILE + (int64_t)wave * S::RW * kRow;
     gfloat* w = (gfloat*)d.w;
     gcfloat* g = (gcfloat*)d.g;
     gbyte* m_q = (gbyte*)d.m_q;
-    float wv[S::RW][4], gv[S::RW][4];
-    uint32_t mq[S::RW];
+    float wv[S::ROWS][4], gv[S::ROWS][4];
+    uint32_t mq[S::ROWS];
+    float Nm_old[S::ROWS];
 #pragma unroll
-    for (int i = 0; i < S::RW; ++i) {
-        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+    for (int r = 0; r < S::ROWS; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(w + e0, cnt, wv[i]);
-            load4f(g + e0, cnt, gv[i]);
-            mq[i] = load4b(m_q + e0, cnt);
+            load4f(w + e0, cnt, wv[r]);
+            load4f(g + e0, cnt, gv[r]);
+            mq[r] = load4b(m_q + e0, cnt);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) { wv[i][j] = 0.0f; gv[i][j] = 0.0f; }
-            mq[i] = 0;
+            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
+            mq[r] = 0;
         }
+        Nm_old[r] = load_block_max<B, FULL>((gcfloat*)d.N_m, n, base, r, lane);
     }
-    const float Nm_old = load_block_max<B, FULL>((gcfloat*)d.N_m, n, row0, lane);
-    uint32_t amax[1] = {0u};
+    uint32_t amax_m[S::NBLK];
 #pragma unroll
-    for (int i = 0; i < S::RW; ++i) {
-        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+    for (int s = 0; s < S::NBLK; ++s) amax_m[s] = 0;
+#pragma unroll
+    for (int r = 0; r < S::ROWS; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m_prev = dequant<false>(lds, (mq[i] >> (8 * j)) & 0xff, Nm_old);
+            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
             float m_new;
-            sgd_element<WD>(sc, wv[i][j], gv[i][j], m_prev, m_new);
+            sgd_element<WD>(sc, wv[r][j], gv[r][j], m_prev, m_new);
             if (!FULL && j >= cnt) m_new = 0.0f;
-            gv[i][j] = m_new;
-            amax[0] = max(amax[0], __float_as_uint(m_new) & 0x7fffffffu);
+            gv[r][j] = m_new;
+            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
         }
-        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[i]);
+        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
     }
-    amax[0] = group_max<S::GROUP>(amax[0], lane);
-    block_max<S::WPB, 1>(ex, parity, wave, lane, amax);
-    requantize_rows<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, row0, wave, lane);
+    requantize_store<B, FULL, false>(lds, gv, amax_m, m_q, (gfloat*)d.N_m, n, base, lane);
 }
 
-// Tensors that keep 32-bit states: same formulas, no quantization, no barrier.
+// Tensors that keep 32-bit states: same formulas, no quantization.  Processed
+// in the same wave tiles.
 template <bool ADAM>
 __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t tile, int tile_elems,
-                                         const AdamScalars& as, const SgdScalars& ss, int wave, int lane)
+                                         const AdamScalars& as, const SgdScalars& ss, int lane)
 {
+    const int64_t base = tile * tile_elems;
     const int64_t n = d.n;
-    const int rw = tile_elems / (kWavesPerWg * kRow);
-    const int64_t row0 = tile * tile_elems + (int64_t)wave * rw * kRow;
     gfloat* w = (gfloat*)d.w;
     gcfloat* g = (gcfloat*)d.g;
     gfloat* m = (gfloat*)d.m_f32;
     gfloat* rr = (gfloat*)d.r_f32;
-    for (int i = 0; i < rw; ++i) {
-        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+    for (int r = 0; r < tile_elems / kRow; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = lane_count(n, e0);
         if (cnt == 0) continue;
         float wv[4], gv[4], mv[4], rv[4] = {0.f, 0.f, 0.f, 0.f};
@@ -547,40 +537,63 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t tile, int 
 
 template <int B, bool FULL>
 __device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int64_t n, int64_t tile,
-                                           const unsigned char* lds, Exchange* ex, int parity, int wave, int lane)
+                                           const unsigned char* lds, int lane)
 {
     using S = Shape<B>;
-    const int64_t row0 = tile * S::TILE + (int64_t)wave * S::RW * kRow;
-    float v[S::RW][4];
-    uint32_t amax[1] = {0u};
+    const int64_t base = tile * S::TILE;
+    float v[S::ROWS][4];
+    uint32_t amax[S::NBLK];
 #pragma unroll
-    for (int i = 0; i < S::RW; ++i) {
-        const int64_t e0 = row0 + (int64_t)i * kRow + lane * 4;
+    for (int s = 0; s < S::NBLK; ++s) amax[s] = 0;
+#pragma unroll
+    for (int r = 0; r < S::ROWS; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(T + e0, cnt, v[i]);
+            load4f(T + e0, cnt, v[r]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[i][j] = 0.0f;
+            for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) amax[0] = max(amax[0], __float_as_uint(v[i][j]) & 0x7fffffffu);
+        for (int j = 0; j < 4; ++j)
+            amax[r / S::RPB] = max(amax[r / S::RPB], __float_as_uint(v[r][j]) & 0x7fffffffu);
     }
-    amax[0] = group_max<S::GROUP>(amax[0], lane);
-    block_max<S::WPB, 1>(ex, parity, wave, lane, amax);
-    requantize_rows<B, FULL, false>(lds, v, amax[0], TQ, N, n, row0, wave, lane);
+    requantize_store<B, FULL, false>(lds, v, amax, TQ, N, n, base, lane);
 }
 
 // ---------------------------------------------------------------------------
-// Persistent tile walk.  Workgroup ids are dealt round-robin to the 8 XCDs, so
-// ids are re-numbered to give every XCD one contiguous run of tiles per pass.
+// Dynamic tile scheduling.  A job is kWavesPerWg consecutive tiles, one per
+// wave.  Thread 0 of a workgroup draws the next job index from `sched->next`
+// and publishes it through LDS (two slots used alternately, so one barrier per
+// job suffices).  Every workgroup leaves the loop at its first out-of-range
+// job; the last one to leave (counted in `sched->done`) zeroes both counters,
+// so the slot is ready for the next launch that uses it.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ int64_t first_tile()
+struct Sched { unsigned long long next, done; };
+
+struct JobBox { long long job[2]; };
+
+__device__ __forceinline__ int64_t next_job(Sched* sched, JobBox* box, int parity)
 {
-    const int G = gridDim.x;
-    int vb = blockIdx.x;
-    if ((G & 7) == 0) vb = (blockIdx.x & 7) * (G >> 3) + (blockIdx.x >> 3);
-    return vb;
+    if (threadIdx.x == 0)
+        box->job[parity] = (long long)atomicAdd(&sched->next, 1ULL);
+    __syncthreads();
+    const long long j = box->job[parity];
+    const int lo = __builtin_amdgcn_readfirstlane((int)j);
+    const int hi = __builtin_amdgcn_readfirstlane((int)(j >> 32));
+    return ((int64_t)hi << 32) | (uint32_t)lo;
+}
+
+__device__ __forceinline__ void leave(Sched* sched)
+{
+    if (threadIdx.x == 0) {
+        const unsigned long long before = atomicAdd(&sched->done, 1ULL);
+        if (before == gridDim.x - 1) {
+            atomicExch(&sched->next, 0ULL);
+            atomicExch(&sched->done, 0ULL);
+        }
+    }
 }
 
 struct StepArgs {
@@ -590,6 +603,7 @@ struct StepArgs {
     int64_t ntiles;
     const void* qtab_s;
     const void* qtab_u;
+    Sched* sched;
 };
 
 // Tile -> (tensor descriptor, tile index inside the tensor).  The tables are read
@@ -622,7 +636,7 @@ static_assert(sizeof(TensorDesc) == 72 && sizeof(TileRef) == 8, "descriptor layo
 
 struct Lds {
     unsigned char tab[kLdsBytes];
-    Exchange ex;
+    JobBox box;
 };
 
 template <int B, int WD>
@@ -631,22 +645,25 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     SgdScalars none{};
-    int parity = 0;
-    for (int64_t t = first_tile(); t < a.ntiles; t += gridDim.x, parity ^= 1) {
+    for (int parity = 0;; parity ^= 1) {
+        const int64_t first = next_job(a.sched, &lds->box, parity) * kWavesPerWg;
+        if (first >= a.ntiles) break;
+        const int64_t t = first + wave;
+        if (t >= a.ntiles) continue;
         int64_t tt;
         const TensorDesc d = resolve(a, t, tt);
         if (d.m_f32) {
-            f32_tile<true>(d, tt, Shape<B>::TILE, sc, none, wave, lane);
+            f32_tile<true>(d, tt, Shape<B>::TILE, sc, none, lane);
         } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
-            adam8_tile<B, true, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
+            adam8_tile<B, true, WD>(d, tt, lds->tab, sc, lane);
         } else {
-            adam8_tile<B, false, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
+            adam8_tile<B, false, WD>(d, tt, lds->tab, sc, lane);
         }
     }
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads) void adam8_kernel(StepArgs a, AdamScalars sc)
+__global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -655,6 +672,7 @@ __global__ __launch_bounds__(kWgThreads) void adam8_kernel(StepArgs a, AdamScala
     if (sc.wd_mode == 0) adam8_walk<B, 0>(a, sc, &lds);
     else if (sc.wd_mode == 1) adam8_walk<B, 1>(a, sc, &lds);
     else adam8_walk<B, 2>(a, sc, &lds);
+    leave(a.sched);
 }
 
 template <int B, bool WD>
@@ -663,46 +681,53 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     AdamScalars none{};
-    int parity = 0;
-    for (int64_t t = first_tile(); t < a.ntiles; t += gridDim.x, parity ^= 1) {
+    for (int parity = 0;; parity ^= 1) {
+        const int64_t first = next_job(a.sched, &lds->box, parity) * kWavesPerWg;
+        if (first >= a.ntiles) break;
+        const int64_t t = first + wave;
+        if (t >= a.ntiles) continue;
         int64_t tt;
         const TensorDesc d = resolve(a, t, tt);
         if (d.m_f32) {
-            f32_tile<false>(d, tt, Shape<B>::TILE, none, sc, wave, lane);
+            f32_tile<false>(d, tt, Shape<B>::TILE, none, sc, lane);
         } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
-            sgd8_tile<B, true, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
+            sgd8_tile<B, true, WD>(d, tt, lds->tab, sc, lane);
         } else {
-            sgd8_tile<B, false, WD>(d, tt, lds->tab, &lds->ex, parity, sc, wave, lane);
+            sgd8_tile<B, false, WD>(d, tt, lds->tab, sc, lane);
         }
     }
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads) void sgd8_kernel(StepArgs a, SgdScalars sc)
+__global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     __syncthreads();
     if (sc.wd != 0.0f) sgd8_walk<B, true>(a, sc, &lds);
     else sgd8_walk<B, false>(a, sc, &lds);
+    leave(a.sched);
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads) void quantize_kernel(const void* qtab, const float* T, uint8_t* TQ,
-                                                              float* N, int64_t n, int64_t ntiles)
+__global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void quantize_kernel(const void* qtab, const float* T,
+                                                                              uint8_t* TQ, float* N, int64_t n,
+                                                                              int64_t ntiles, Sched* sched)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, qtab, threadIdx.x);
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    int parity = 0;
-    for (int64_t t = first_tile(); t < ntiles; t += gridDim.x, parity ^= 1) {
-        if ((t + 1) * Shape<B>::TILE <= n)
-            quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, &lds.ex, parity, wave, lane);
-        else
-            quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, &lds.ex, parity, wave, lane);
+    for (int parity = 0;; parity ^= 1) {
+        const int64_t first = next_job(sched, &lds.box, parity) * kWavesPerWg;
+        if (first >= ntiles) break;
+        const int64_t t = first + wave;
+        if (t >= ntiles) continue;
+        if ((t + 1) * Shape<B>::TILE <= n) quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, lane);
+        else quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, lane);
     }
+    leave(sched);
 }
 
 // Eq. quant3.  One thread handles 4 consecutive elements per step; the block
@@ -738,7 +763,14 @@ bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) &
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 int tile_elems(int B) { return B > 2048 ? B : 2048; }
 
-struct DeviceInfo { int cus; };
+// Job counters of the dynamic scheduler: a ring of slots in device memory that
+// launches use in turn.  A kernel leaves its slot zeroed, so consecutive launches
+// on one stream may share a slot; launches that overlap on different streams get
+// different slots unless more than kSchedSlots of them are in flight at once.
+constexpr int kSchedSlots = 64;
+__device__ Sched g_sched[kSchedSlots];
+
+struct DeviceInfo { int cus; Sched* sched; };
 
 q8_status device_info(DeviceInfo& out)
 {
@@ -750,18 +782,27 @@ q8_status device_info(DeviceInfo& out)
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             return Q8_ELAUNCH;
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess || !p) return Q8_ELAUNCH;
         cached.cus = cus;
+        cached.sched = static_cast<Sched*>(p);
         cached_dev = dev;
     }
     out = cached;
     return Q8_OK;
 }
 
+Sched* next_sched_slot(const DeviceInfo& di)
+{
+    static std::atomic<unsigned> turn{0};
+    return di.sched + (turn.fetch_add(1) % kSchedSlots);
+}
+
 // Persistent grid: enough workgroups to fill every CU to the kernel's
-// occupancy, never more than there are tiles.
+// occupancy, never more than there are jobs (kWavesPerWg tiles each).
 // `per_cu` caches the occupancy query of one kernel (0 = not asked yet).
 template <typename K>
-q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid)
+q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid, Sched** slot)
 {
     DeviceInfo di;
     q8_status st = device_info(di);
@@ -772,10 +813,11 @@ q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid)
             return Q8_ELAUNCH;
         per_cu = v;
     }
-    int64_t want = ntiles;                 // one workgroup step per tile
+    int64_t want = (ntiles + kWavesPerWg - 1) / kWavesPerWg;
     int64_t cap = (int64_t)di.cus * per_cu;
     grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
+    *slot = next_sched_slot(di);
     return Q8_OK;
 }
 
@@ -829,22 +871,22 @@ q8_status make_adam_scalars(float alpha, float beta1, float beta2, float eps, fl
 }
 
 template <int B>
-q8_status launch_adam(const StepArgs& a, const AdamScalars& sc, hipStream_t stream)
+q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 {
     static int per_cu = 0;
     int grid;
-    q8_status st = grid_for(adam8_kernel<B>, per_cu, a.ntiles, grid);
+    q8_status st = grid_for(adam8_kernel<B>, per_cu, a.ntiles, grid, &a.sched);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL(adam8_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
 }
 
 template <int B>
-q8_status launch_sgd(const StepArgs& a, const SgdScalars& sc, hipStream_t stream)
+q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 {
     static int per_cu = 0;
     int grid;
-    q8_status st = grid_for(sgd8_kernel<B>, per_cu, a.ntiles, grid);
+    q8_status st = grid_for(sgd8_kernel<B>, per_cu, a.ntiles, grid, &a.sched);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL(sgd8_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
@@ -856,9 +898,10 @@ q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* 
     const int64_t ntiles = (n + Shape<B>::TILE - 1) / Shape<B>::TILE;
     static int per_cu = 0;
     int grid;
-    q8_status st = grid_for(quantize_kernel<B>, per_cu, ntiles, grid);
+    Sched* slot = nullptr;
+    q8_status st = grid_for(quantize_kernel<B>, per_cu, ntiles, grid, &slot);
     if (st != Q8_OK) return st;
-    hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, ntiles);
+    hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, ntiles, slot);
     return launch_status();
 }
 
