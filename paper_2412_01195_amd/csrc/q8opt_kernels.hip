@@ -348,18 +348,22 @@ __device__ __forceinline__ void requantize_store(const unsigned char* lds, float
     }
 }
 
-// Old block maximum for row r of the tile (uniform for B >= 256, per lane group below).
+// Old block maximum for row r of the tile.  For B >= 256 the index is wave-uniform
+// and the value is read with a scalar load: the entry was written by an earlier
+// launch (or, later in this launch, only by this very wave), so the scalar cache
+// cannot hold a stale copy.  Below 256 each lane group reads its own block.
+#define Q8_CONSTANT __attribute__((address_space(4)))
 template <int B, bool FULL>
-__device__ __forceinline__ float load_block_max(gcfloat* N, int64_t n, int64_t base, int r, int lane)
+__device__ __forceinline__ float load_block_max(const float* N, int64_t n, int64_t base, int r, int lane)
 {
     const int64_t row0 = base + (int64_t)r * kRow;
     if (B >= kRow) {
         if (!FULL && row0 >= n) return 0.0f;
-        return N[row0 / B];
+        return ((Q8_CONSTANT const float*)N)[row0 / B];
     }
     const int64_t e0 = row0 + lane * 4;
     if (!FULL && e0 >= n) return 0.0f;
-    return N[e0 / B];
+    return ((gcfloat*)N)[e0 / B];
 }
 
 // ---------------------------------------------------------------------------
@@ -458,8 +462,8 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, co
             for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
             mq[r] = 0; rq[r] = 0;
         }
-        Nm_old[r] = load_block_max<B, FULL>((gcfloat*)d.N_m, n, base, r, lane);
-        Nr_old[r] = load_block_max<B, FULL>((gcfloat*)d.N_r, n, base, r, lane);
+        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
+        Nr_old[r] = load_block_max<B, FULL>(d.N_r, n, base, r, lane);
     }
     uint32_t amax_m[S::NBLK], amax_r[S::NBLK];
 #pragma unroll
@@ -527,7 +531,7 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, con
             for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
             mq[r] = 0;
         }
-        Nm_old[r] = load_block_max<B, FULL>((gcfloat*)d.N_m, n, base, r, lane);
+        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
     }
     uint32_t amax_m[S::NBLK];
 #pragma unroll
@@ -662,7 +666,6 @@ struct StepArgs {
 // Tile -> (tensor descriptor, tile index inside the tensor).  The tables are read
 // through the constant address space with wave-uniform indices, i.e. by scalar
 // loads into SGPRs.
-#define Q8_CONSTANT __attribute__((address_space(4)))
 __device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t t, int64_t& tile_in_tensor)
 {
     if (a.tiles) {
@@ -716,7 +719,7 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void adam8_kernel(StepArgs a, AdamScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -752,7 +755,7 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void sgd8_kernel(StepArgs a, SgdScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -763,7 +766,7 @@ __global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void sgd8_kernel(St
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, (B > 2048 ? 2 : 4)) void quantize_kernel(const void* qtab, const float* T,
+__global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void quantize_kernel(const void* qtab, const float* T,
                                                                               uint8_t* TQ, float* N, int64_t n,
                                                                               int64_t ntiles, Sched* sched)
 {
