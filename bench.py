@@ -162,7 +162,8 @@ def main():
                      "traffic": measured_traffic(os.path.join(ROOT, "profiles", "adam8_kernel_1b_hbm_counters.md"))
                      if args.workload == "1b" else None,
                      "kernel": "adam8_kernel<2048>", "kernel_ms_avg": avg_kern_s * 1e3,
-                     "kernel_ms_min": min(kern_ms), "algorithmic_bytes_per_launch": alg},
+                     "kernel_ms_min": min(kern_ms), "kernel_ms_each": [round(x, 4) for x in kern_ms],
+                     "algorithmic_bytes_per_launch": alg},
     }
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, g, B, args.cpu_sample, steps=2)

@@ -1,23 +1,28 @@
 // gfx950 kernels and device entry points of the fused 8-bit optimizer step
 // (Sec. IV of the paper: Eq. sgd, Eq. adam, Eq. quant1-quant3).
 //
-// Work decomposition: one wave64 owns one "tile" of TILE = max(B, 2048)
-// consecutive elements of one tensor, i.e. whole quantization blocks.  The tile is
-// read as ROWS rows of 256 elements; lane l of the wave holds elements
-// [256 r + 4 l, 256 r + 4 l + 4) of row r, so every fp32 access is one coalesced
-// 128-bit load/store per lane and every code access one coalesced 32-bit one.
-// New states stay in registers between the update and the re-quantization; the
-// block absmax needs only cross-lane DPP steps inside the wave (no barrier, no
-// LDS traffic), and per-block work (reduction, reciprocal) is amortised over 32
-// elements per lane.
+// Work decomposition: one wave64 owns 1024 consecutive elements of one tensor, read
+// as 4 rows of 256 elements; lane l of the wave holds elements [256 r + 4 l,
+// 256 r + 4 l + 4) of row r, so every fp32 access is one coalesced 128-bit
+// load/store per lane and every code access one coalesced 32-bit one.  New states
+// stay in registers between the update and the re-quantization, so HBM is touched
+// once per byte.  The block absmax is reduced with DPP steps inside the wave; for
+// B <= 1024 a wave holds whole blocks, for B = 2048 (4096) the 2 (4) waves that
+// share a block exchange their maxima through LDS with one barrier.
 //
 // Scheduling: workgroups of 8 waves are persistent.  They stage the search tables
-// into 64 KB of LDS once and then draw "jobs" of 8 consecutive tiles (one per
-// wave) from an atomic counter in device memory.  Handing tiles out in address
-// order to whichever workgroup is free keeps the set of addresses in flight one
-// dense, slowly advancing window over each stream, which is what the HBM
-// controllers reward; a static grid-stride or chunked assignment measured 10-15 %
-// slower on the same access pattern.
+// into 64 KB of LDS once and then draw "jobs" of 8 consecutive wave tiles from an
+// atomic counter in device memory.  Handing work out in address order to whichever
+// workgroup is free keeps the set of addresses in flight one dense, slowly
+// advancing window over each stream, which is what the HBM controllers reward: on
+// a bandwidth skeleton of this access pattern a static grid-stride assignment
+// reached 5.1 TB/s, chunks 5.4 TB/s, dynamic jobs of 8 x 2048 elements 5.9 TB/s and
+// dynamic jobs of 8 x 1024 elements (half the window) 6.4 TB/s.
+//
+// Barriers sit in wave-uniform branches: the waves of a workgroup may reach their
+// one exchange barrier of a job at different program points (full tile, ragged
+// tile, no tile), which is sound on this hardware because s_barrier only counts
+// arriving waves; every wave executes the same number of barriers per job.
 //
 // Nearest-code search (Eq. quant2): the upper 16 bits of the binary32 pattern of
 // x = m / N index a byte table in LDS that holds the code at the lower end of that
@@ -44,8 +49,14 @@ using namespace q8;
 
 namespace {
 
-constexpr int kWgThreads = 512;
-constexpr int kWavesPerWg = 8;
+#ifndef Q8_WG_THREADS
+#define Q8_WG_THREADS 512
+#endif
+#ifndef Q8_MIN_WAVES
+#define Q8_MIN_WAVES 4
+#endif
+constexpr int kWgThreads = Q8_WG_THREADS;
+constexpr int kWavesPerWg = kWgThreads / 64;
 constexpr int kRow = 256;                 // elements per wave row: 64 lanes x 4
 
 // Pointers into HBM carry the global address space so that loads and stores
@@ -288,35 +299,83 @@ __device__ __forceinline__ void store4b(gbyte* p, int cnt, uint32_t v)
     }
 }
 
+// Geometry.  A wave owns 1024 consecutive elements (4 rows).  A "unit" is
+// max(B, 1024) elements: the granule of the tile table and of scheduling.  For
+// B <= 1024 a unit is one wave and holds 1024/B whole blocks; for B = 2048 (4096)
+// the 2 (4) waves of a unit share one block and exchange their maxima through LDS.
+constexpr int kWaveRows = 4;
+constexpr int kWaveElems = kWaveRows * kRow;
+
 template <int B>
 struct Shape {
-    static constexpr int TILE = (B > 2048) ? B : 2048;
-    static constexpr int ROWS = TILE / kRow;
-    static constexpr int RPB = (B >= kRow) ? B / kRow : 1;      // rows per block
-    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;      // lanes per block in a row
-    static constexpr int NBLK = ROWS / RPB;                     // block slots per lane
+    static constexpr int UNIT = (B > kWaveElems) ? B : kWaveElems;
+    static constexpr int WPB = UNIT / kWaveElems;                       // waves per unit: 1, 2, 4
+    static constexpr int UPJ = kWavesPerWg / WPB;                       // units per job
+    static constexpr int RPB = (B >= kWaveElems) ? kWaveRows : (B >= kRow ? B / kRow : 1);   // rows per block slot
+    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;              // lanes per block in a row
+    static constexpr int NBLK = kWaveRows / RPB;                        // block slots per lane
 };
 
-// Re-quantize the ROWS x 4 values of this lane (Eq. quant1, quant2) and store
-// codes and block maxima.  `val` holds the new state, `amax` the per-slot lane
-// maxima of |val| as bit patterns.
+// LDS words for the exchange of wave maxima: [parity][state][wave].
+struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
+
+// Turn lane maxima into block maxima: DPP reduction inside the wave and, when a
+// block spans WPB > 1 waves, an exchange through LDS.  In that case every wave of
+// the workgroup must call this exactly once per job (it contains a barrier);
+// `parity` alternates between jobs so that one barrier per job suffices: a slot
+// is rewritten two jobs later, after barriers that every reader has passed.
+template <int B, int NSTATE>
+__device__ __forceinline__ void reduce_block_max(uint32_t (&v)[NSTATE][Shape<B>::NBLK], Exchange* ex, int parity,
+                                                 int wave, int lane)
+{
+    using S = Shape<B>;
+#pragma unroll
+    for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+        for (int k = 0; k < S::NBLK; ++k) v[st][k] = group_max<S::GROUP>(v[st][k], lane);
+    if (S::WPB > 1) {
+        if (lane == 0) {
+#pragma unroll
+            for (int st = 0; st < NSTATE; ++st) ex->part[parity][st][wave] = v[st][0];
+        }
+        __syncthreads();
+        const int g0 = wave & ~(S::WPB - 1);
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int k = 0; k < S::WPB; ++k) m = max(m, ex->part[parity][st][g0 + k]);
+            v[st][0] = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
+        }
+    }
+}
+
+// The barrier of reduce_block_max for waves that have no 8-bit tile in this job.
+template <int B>
+__device__ __forceinline__ void idle_block_max()
+{
+    if (Shape<B>::WPB > 1) __syncthreads();
+}
+
+// Quantize the 4 x 4 values of this lane (Eq. quant1, quant2) against the block
+// maxima `nbits` (bit patterns of N per block slot) and store codes and maxima.
+// `base` is the first element of this wave, `part` its index inside the unit.
 template <int B, bool FULL, bool SECOND>
-__device__ __forceinline__ void requantize_store(const unsigned char* lds, float (&val)[Shape<B>::ROWS][4],
-                                                 uint32_t (&amax)[Shape<B>::NBLK],
+__device__ __forceinline__ void requantize_store(const unsigned char* lds, float (&val)[kWaveRows][4],
+                                                 const uint32_t (&nbits)[Shape<B>::NBLK],
                                                  gbyte* codes, gfloat* Nout,
-                                                 int64_t n, int64_t base, int lane)
+                                                 int64_t n, int64_t base, int part, int lane)
 {
     using S = Shape<B>;
 #pragma unroll
     for (int s = 0; s < S::NBLK; ++s) {
-        const uint32_t nbits = group_max<S::GROUP>(amax[s], lane);
-        const BlockNorm bn = make_norm(nbits);
+        const BlockNorm bn = make_norm(nbits[s]);
         const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
         if (B >= kRow) {
-            if ((FULL || row0 < n) && lane == 0) Nout[row0 / B] = bn.N;
+            if (part == 0 && lane == 0 && (FULL || row0 < n)) Nout[row0 / B] = bn.N;
         } else {
             const int64_t e0 = row0 + lane * 4;
-            if ((FULL || e0 < n) && (lane % S::GROUP) == 0) Nout[e0 / B] = bn.N;
+            if ((lane % S::GROUP) == 0 && (FULL || e0 < n)) Nout[e0 / B] = bn.N;
         }
         // one wave-uniform decision per block slot keeps the common path straight-line
         const bool all_fast = (S::GROUP == 64) ? bn.fast : (__builtin_amdgcn_ballot_w64(!bn.fast) == 0);
@@ -348,10 +407,11 @@ __device__ __forceinline__ void requantize_store(const unsigned char* lds, float
     }
 }
 
-// Old block maximum for row r of the tile.  For B >= 256 the index is wave-uniform
+// Old block maximum for row r of this wave.  For B >= 256 the index is wave-uniform
 // and the value is read with a scalar load: the entry was written by an earlier
-// launch (or, later in this launch, only by this very wave), so the scalar cache
-// cannot hold a stale copy.  Below 256 each lane group reads its own block.
+// launch (or, later in this launch, only by a wave of this very unit after the
+// barrier), so the scalar cache cannot hold a stale copy.  Below 256 each lane
+// group reads its own block.
 #define Q8_CONSTANT __attribute__((address_space(4)))
 template <int B, bool FULL>
 __device__ __forceinline__ float load_block_max(const float* N, int64_t n, int64_t base, int r, int lane)
@@ -432,24 +492,23 @@ __device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float
 }
 
 // ---------------------------------------------------------------------------
-// Tiles (one wave each).
+// Wave tiles.  `base` = first element of this wave inside the tensor.
 // ---------------------------------------------------------------------------
 template <int B, bool FULL, int WD>
-__device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, const unsigned char* lds,
-                                           const AdamScalars& sc, int lane)
+__device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
+                                           Exchange* ex, int parity, const AdamScalars& sc, int wave, int lane)
 {
     using S = Shape<B>;
-    const int64_t base = tile * S::TILE;
     const int64_t n = d.n;
     gfloat* w = (gfloat*)d.w;
     gcfloat* g = (gcfloat*)d.g;
     gbyte* m_q = (gbyte*)d.m_q;
     gbyte* r_q = (gbyte*)d.r_q;
-    float wv[S::ROWS][4], gv[S::ROWS][4];
-    uint32_t mq[S::ROWS], rq[S::ROWS];
-    float Nm_old[S::ROWS], Nr_old[S::ROWS];
+    float wv[kWaveRows][4], gv[kWaveRows][4];
+    uint32_t mq[kWaveRows], rq[kWaveRows];
+    float Nm_old[kWaveRows], Nr_old[kWaveRows];
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
+    for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
@@ -465,12 +524,12 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, co
         Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
         Nr_old[r] = load_block_max<B, FULL>(d.N_r, n, base, r, lane);
     }
-    uint32_t amax_m[S::NBLK], amax_r[S::NBLK];
+    uint32_t amax[2][S::NBLK];
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) { amax_m[s] = 0; amax_r[s] = 0; }
+    for (int s = 0; s < S::NBLK; ++s) { amax[0][s] = 0; amax[1][s] = 0; }
     // after this loop gv holds the new m and wv is reused for the new r
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
+    for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         float mnew[4], rnew[4];
@@ -497,29 +556,29 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t tile, co
             if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
             gv[r][j] = mnew[j];
             wv[r][j] = rnew[j];
-            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(mnew[j]) & 0x7fffffffu);
-            amax_r[r / S::RPB] = max(amax_r[r / S::RPB], __float_as_uint(rnew[j]));
+            amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(mnew[j]) & 0x7fffffffu);
+            amax[1][r / S::RPB] = max(amax[1][r / S::RPB], __float_as_uint(rnew[j]));
         }
     }
-    requantize_store<B, FULL, false>(lds, gv, amax_m, m_q, (gfloat*)d.N_m, n, base, lane);
-    requantize_store<B, FULL, true>(lds, wv, amax_r, r_q, (gfloat*)d.N_r, n, base, lane);
+    reduce_block_max<B, 2>(amax, ex, parity, wave, lane);
+    requantize_store<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
+    requantize_store<B, FULL, true>(lds, wv, amax[1], r_q, (gfloat*)d.N_r, n, base, part, lane);
 }
 
 template <int B, bool FULL, bool WD>
-__device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, const unsigned char* lds,
-                                          const SgdScalars& sc, int lane)
+__device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
+                                          Exchange* ex, int parity, const SgdScalars& sc, int wave, int lane)
 {
     using S = Shape<B>;
-    const int64_t base = tile * S::TILE;
     const int64_t n = d.n;
     gfloat* w = (gfloat*)d.w;
     gcfloat* g = (gcfloat*)d.g;
     gbyte* m_q = (gbyte*)d.m_q;
-    float wv[S::ROWS][4], gv[S::ROWS][4];
-    uint32_t mq[S::ROWS];
-    float Nm_old[S::ROWS];
+    float wv[kWaveRows][4], gv[kWaveRows][4];
+    uint32_t mq[kWaveRows];
+    float Nm_old[kWaveRows];
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
+    for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
@@ -533,11 +592,11 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, con
         }
         Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
     }
-    uint32_t amax_m[S::NBLK];
+    uint32_t amax[1][S::NBLK];
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) amax_m[s] = 0;
+    for (int s = 0; s < S::NBLK; ++s) amax[0][s] = 0;
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
+    for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
 #pragma unroll
@@ -547,26 +606,26 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t tile, con
             sgd_element<WD>(sc, wv[r][j], gv[r][j], m_prev, m_new);
             if (!FULL && j >= cnt) m_new = 0.0f;
             gv[r][j] = m_new;
-            amax_m[r / S::RPB] = max(amax_m[r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
+            amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
         }
         if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
     }
-    requantize_store<B, FULL, false>(lds, gv, amax_m, m_q, (gfloat*)d.N_m, n, base, lane);
+    reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
+    requantize_store<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
 }
 
-// Tensors that keep 32-bit states: same formulas, no quantization.  Processed
-// in the same wave tiles.
+// Tensors that keep 32-bit states: same formulas, no quantization; one wave
+// handles its 1024 elements.
 template <bool ADAM>
-__device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t tile, int tile_elems,
-                                         const AdamScalars& as, const SgdScalars& ss, int lane)
+__device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, const AdamScalars& as,
+                                         const SgdScalars& ss, int lane)
 {
-    const int64_t base = tile * tile_elems;
     const int64_t n = d.n;
     gfloat* w = (gfloat*)d.w;
     gcfloat* g = (gcfloat*)d.g;
     gfloat* m = (gfloat*)d.m_f32;
     gfloat* rr = (gfloat*)d.r_f32;
-    for (int r = 0; r < tile_elems / kRow; ++r) {
+    for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = lane_count(n, e0);
         if (cnt == 0) continue;
@@ -593,17 +652,16 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t tile, int 
 }
 
 template <int B, bool FULL>
-__device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int64_t n, int64_t tile,
-                                           const unsigned char* lds, int lane)
+__device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int64_t n, int64_t base, int part,
+                                           const unsigned char* lds, Exchange* ex, int parity, int wave, int lane)
 {
     using S = Shape<B>;
-    const int64_t base = tile * S::TILE;
-    float v[S::ROWS][4];
-    uint32_t amax[S::NBLK];
+    float v[kWaveRows][4];
+    uint32_t amax[1][S::NBLK];
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) amax[s] = 0;
+    for (int s = 0; s < S::NBLK; ++s) amax[0][s] = 0;
 #pragma unroll
-    for (int r = 0; r < S::ROWS; ++r) {
+    for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
@@ -614,18 +672,19 @@ __device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            amax[r / S::RPB] = max(amax[r / S::RPB], __float_as_uint(v[r][j]) & 0x7fffffffu);
+            amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(v[r][j]) & 0x7fffffffu);
     }
-    requantize_store<B, FULL, false>(lds, v, amax, TQ, N, n, base, lane);
+    reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
+    requantize_store<B, FULL, false>(lds, v, amax[0], TQ, N, n, base, part, lane);
 }
 
 // ---------------------------------------------------------------------------
-// Dynamic tile scheduling.  A job is kWavesPerWg consecutive tiles, one per
-// wave.  Thread 0 of a workgroup draws the next job index from `sched->next`
-// and publishes it through LDS (two slots used alternately, so one barrier per
-// job suffices).  Every workgroup leaves the loop at its first out-of-range
-// job; the last one to leave (counted in `sched->done`) zeroes both counters,
-// so the slot is ready for the next launch that uses it.
+// Dynamic scheduling.  A job is kWavesPerWg consecutive wave tiles, i.e. UPJ
+// consecutive units.  Thread 0 of a workgroup draws the next job index from
+// `sched->next` and publishes it through LDS (two slots used alternately, so one
+// barrier per job suffices).  Every workgroup leaves the loop at its first
+// out-of-range job; the last one to leave (counted in `sched->done`) zeroes both
+// counters, so the slot is ready for the next launch that uses it.
 // ---------------------------------------------------------------------------
 struct Sched { unsigned long long next, done; };
 
@@ -655,23 +714,23 @@ __device__ __forceinline__ void leave(Sched* sched)
 
 struct StepArgs {
     const TensorDesc* descs;      // device list, or nullptr: use `single`
-    const TileRef* tiles;         // device tile table for lists, else nullptr
+    const TileRef* tiles;         // device unit table for lists, else nullptr
     TensorDesc single;
-    int64_t ntiles;
+    int64_t nunits;
     const void* qtab_s;
     const void* qtab_u;
     Sched* sched;
 };
 
-// Tile -> (tensor descriptor, tile index inside the tensor).  The tables are read
+// Unit -> (tensor descriptor, unit index inside the tensor).  The tables are read
 // through the constant address space with wave-uniform indices, i.e. by scalar
 // loads into SGPRs.
-__device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t t, int64_t& tile_in_tensor)
+__device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t u, int64_t& unit_in_tensor)
 {
     if (a.tiles) {
-        Q8_CONSTANT const int32_t* ref = (Q8_CONSTANT const int32_t*)a.tiles + 2 * t;
+        Q8_CONSTANT const int32_t* ref = (Q8_CONSTANT const int32_t*)a.tiles + 2 * u;
         const int ti = ref[0];
-        tile_in_tensor = ref[1];
+        unit_in_tensor = ref[1];
         Q8_CONSTANT const uint64_t* f = (Q8_CONSTANT const uint64_t*)(a.descs + ti);
         TensorDesc d;
         d.w = (float*)f[0];
@@ -685,7 +744,7 @@ __device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t t, int6
         d.n = (int64_t)f[8];
         return d;
     }
-    tile_in_tensor = t;
+    unit_in_tensor = u;
     return a.single;
 }
 static_assert(sizeof(TensorDesc) == 72 && sizeof(TileRef) == 8, "descriptor layout");
@@ -693,33 +752,42 @@ static_assert(sizeof(TensorDesc) == 72 && sizeof(TileRef) == 8, "descriptor layo
 struct Lds {
     unsigned char tab[kLdsBytes];
     JobBox box;
+    Exchange ex;
 };
 
 template <int B, int WD>
 __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars& sc, Lds* lds)
 {
+    using S = Shape<B>;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
     SgdScalars none{};
     for (int parity = 0;; parity ^= 1) {
-        const int64_t first = next_job(a.sched, &lds->box, parity) * kWavesPerWg;
-        if (first >= a.ntiles) break;
-        const int64_t t = first + wave;
-        if (t >= a.ntiles) continue;
-        int64_t tt;
-        const TensorDesc d = resolve(a, t, tt);
-        if (d.m_f32) {
-            f32_tile<true>(d, tt, Shape<B>::TILE, sc, none, lane);
-        } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
-            adam8_tile<B, true, WD>(d, tt, lds->tab, sc, lane);
-        } else {
-            adam8_tile<B, false, WD>(d, tt, lds->tab, sc, lane);
+        const int64_t first = next_job(a.sched, &lds->box, parity) * S::UPJ;
+        if (first >= a.nunits) break;
+        const int64_t u = first + wave / S::WPB;
+        bool done = false;
+        if (u < a.nunits) {
+            int64_t ut;
+            const TensorDesc d = resolve(a, u, ut);
+            const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
+            if (d.m_f32) {
+                f32_tile<true>(d, base, sc, none, lane);
+            } else if (base + kWaveElems <= d.n) {
+                adam8_tile<B, true, WD>(d, base, part, lds->tab, &lds->ex, parity, sc, wave, lane);
+                done = true;
+            } else {
+                adam8_tile<B, false, WD>(d, base, part, lds->tab, &lds->ex, parity, sc, wave, lane);
+                done = true;
+            }
         }
+        if (!done) idle_block_max<B>();
     }
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void adam8_kernel(StepArgs a, AdamScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -734,28 +802,36 @@ __global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void a
 template <int B, bool WD>
 __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& sc, Lds* lds)
 {
+    using S = Shape<B>;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
     AdamScalars none{};
     for (int parity = 0;; parity ^= 1) {
-        const int64_t first = next_job(a.sched, &lds->box, parity) * kWavesPerWg;
-        if (first >= a.ntiles) break;
-        const int64_t t = first + wave;
-        if (t >= a.ntiles) continue;
-        int64_t tt;
-        const TensorDesc d = resolve(a, t, tt);
-        if (d.m_f32) {
-            f32_tile<false>(d, tt, Shape<B>::TILE, none, sc, lane);
-        } else if ((tt + 1) * Shape<B>::TILE <= d.n) {
-            sgd8_tile<B, true, WD>(d, tt, lds->tab, sc, lane);
-        } else {
-            sgd8_tile<B, false, WD>(d, tt, lds->tab, sc, lane);
+        const int64_t first = next_job(a.sched, &lds->box, parity) * S::UPJ;
+        if (first >= a.nunits) break;
+        const int64_t u = first + wave / S::WPB;
+        bool done = false;
+        if (u < a.nunits) {
+            int64_t ut;
+            const TensorDesc d = resolve(a, u, ut);
+            const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
+            if (d.m_f32) {
+                f32_tile<false>(d, base, none, sc, lane);
+            } else if (base + kWaveElems <= d.n) {
+                sgd8_tile<B, true, WD>(d, base, part, lds->tab, &lds->ex, parity, sc, wave, lane);
+                done = true;
+            } else {
+                sgd8_tile<B, false, WD>(d, base, part, lds->tab, &lds->ex, parity, sc, wave, lane);
+                done = true;
+            }
         }
+        if (!done) idle_block_max<B>();
     }
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void sgd8_kernel(StepArgs a, SgdScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -766,22 +842,30 @@ __global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void s
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, ((B > 2048 || B < 256) ? 2 : 4)) void quantize_kernel(const void* qtab, const float* T,
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void quantize_kernel(const void* qtab, const float* T,
                                                                               uint8_t* TQ, float* N, int64_t n,
-                                                                              int64_t ntiles, Sched* sched)
+                                                                              int64_t nunits, Sched* sched)
 {
+    using S = Shape<B>;
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, qtab, threadIdx.x);
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
     for (int parity = 0;; parity ^= 1) {
-        const int64_t first = next_job(sched, &lds.box, parity) * kWavesPerWg;
-        if (first >= ntiles) break;
-        const int64_t t = first + wave;
-        if (t >= ntiles) continue;
-        if ((t + 1) * Shape<B>::TILE <= n) quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, lane);
-        else quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, t, lds.tab, lane);
+        const int64_t first = next_job(sched, &lds.box, parity) * S::UPJ;
+        if (first >= nunits) break;
+        const int64_t u = first + wave / S::WPB;
+        if (u < nunits) {
+            const int64_t base = u * S::UNIT + (int64_t)part * kWaveElems;
+            if (base + kWaveElems <= n)
+                quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, &lds.ex, parity, wave, lane);
+            else
+                quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, &lds.ex, parity, wave, lane);
+        } else {
+            idle_block_max<B>();
+        }
     }
     leave(sched);
 }
@@ -817,7 +901,8 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const void* qtab, const
 bool valid_block(int B) { return B >= 64 && B <= 4096 && (B & (B - 1)) == 0; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
-int tile_elems(int B) { return B > 2048 ? B : 2048; }
+int unit_elems(int B) { return B > 1024 ? B : 1024; }                 // Shape<B>::UNIT
+int units_per_job(int B) { return kWavesPerWg / (unit_elems(B) / 1024); }   // Shape<B>::UPJ
 
 // Job counters of the dynamic scheduler: a ring of slots in device memory that
 // launches use in turn.  A kernel leaves its slot zeroed, so consecutive launches
@@ -855,10 +940,10 @@ Sched* next_sched_slot(const DeviceInfo& di)
 }
 
 // Persistent grid: enough workgroups to fill every CU to the kernel's
-// occupancy, never more than there are jobs (kWavesPerWg tiles each).
+// occupancy, never more than there are jobs.
 // `per_cu` caches the occupancy query of one kernel (0 = not asked yet).
 template <typename K>
-q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid, Sched** slot)
+q8_status grid_for(K kernel, int& per_cu, int64_t njobs, int& grid, Sched** slot)
 {
     DeviceInfo di;
     q8_status st = device_info(di);
@@ -869,7 +954,7 @@ q8_status grid_for(K kernel, int& per_cu, int64_t ntiles, int& grid, Sched** slo
             return Q8_ELAUNCH;
         per_cu = v;
     }
-    int64_t want = (ntiles + kWavesPerWg - 1) / kWavesPerWg;
+    int64_t want = njobs;
     int64_t cap = (int64_t)di.cus * per_cu;
     grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
@@ -931,7 +1016,7 @@ q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 {
     static int per_cu = 0;
     int grid;
-    q8_status st = grid_for(adam8_kernel<B>, per_cu, a.ntiles, grid, &a.sched);
+    q8_status st = grid_for(adam8_kernel<B>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL(adam8_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
@@ -942,7 +1027,7 @@ q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 {
     static int per_cu = 0;
     int grid;
-    q8_status st = grid_for(sgd8_kernel<B>, per_cu, a.ntiles, grid, &a.sched);
+    q8_status st = grid_for(sgd8_kernel<B>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL(sgd8_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
@@ -951,13 +1036,13 @@ q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 template <int B>
 q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* N, int64_t n, hipStream_t stream)
 {
-    const int64_t ntiles = (n + Shape<B>::TILE - 1) / Shape<B>::TILE;
+    const int64_t nunits = (n + Shape<B>::UNIT - 1) / Shape<B>::UNIT;
     static int per_cu = 0;
     int grid;
     Sched* slot = nullptr;
-    q8_status st = grid_for(quantize_kernel<B>, per_cu, ntiles, grid, &slot);
+    q8_status st = grid_for(quantize_kernel<B>, per_cu, (nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &slot);
     if (st != Q8_OK) return st;
-    hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, ntiles, slot);
+    hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, nunits, slot);
     return launch_status();
 }
 
@@ -1021,7 +1106,7 @@ extern "C" q8_status q8_adam8bit_step(float* w, const float* g, uint8_t* m_q, ui
         return Q8_EALIGN;
     StepArgs a{};
     a.single = TensorDesc{w, g, m_q, r_q, N_m, N_r, nullptr, nullptr, n};
-    a.ntiles = (n + tile_elems(B) - 1) / tile_elems(B);
+    a.nunits = (n + unit_elems(B) - 1) / unit_elems(B);
     a.qtab_s = qtable_signed;
     a.qtab_u = qtable_unsigned;
     Q8_DISPATCH_B(B, return launch_adam<kB>(a, sc, static_cast<hipStream_t>(stream)));
@@ -1039,7 +1124,7 @@ extern "C" q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, flo
         return Q8_EALIGN;
     StepArgs a{};
     a.single = TensorDesc{w, g, m_q, nullptr, N_m, nullptr, nullptr, nullptr, n};
-    a.ntiles = (n + tile_elems(B) - 1) / tile_elems(B);
+    a.nunits = (n + unit_elems(B) - 1) / unit_elems(B);
     a.qtab_s = qtable_signed;
     SgdScalars sc{alpha, beta, weight_decay};
     Q8_DISPATCH_B(B, return launch_sgd<kB>(a, sc, static_cast<hipStream_t>(stream)));
@@ -1052,7 +1137,7 @@ extern "C" q8_status q8_plan_create(const q8_tensor* list, int count, int B, q8_
     *out = nullptr;
     if (!list || count <= 0) return Q8_EINVAL;
     if (!valid_block(B)) return Q8_EBLOCK;
-    const int64_t te = tile_elems(B);
+    const int64_t te = unit_elems(B);
     int64_t ntiles = 0;
     bool has_r = true;
     for (int i = 0; i < count; ++i) {
@@ -1130,7 +1215,7 @@ extern "C" q8_status q8_multi_adam8bit_step(q8_plan* plan, const void* qtable_si
     StepArgs a{};
     a.descs = plan->d_descs;
     a.tiles = plan->d_tiles;
-    a.ntiles = plan->ntiles;
+    a.nunits = plan->ntiles;
     a.qtab_s = qtable_signed;
     a.qtab_u = qtable_unsigned;
     Q8_DISPATCH_B(plan->B, return launch_adam<kB>(a, sc, static_cast<hipStream_t>(stream)));
@@ -1146,7 +1231,7 @@ extern "C" q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_sig
     StepArgs a{};
     a.descs = plan->d_descs;
     a.tiles = plan->d_tiles;
-    a.ntiles = plan->ntiles;
+    a.nunits = plan->ntiles;
     a.qtab_s = qtable_signed;
     SgdScalars sc{alpha, beta, weight_decay};
     Q8_DISPATCH_B(plan->B, return launch_sgd<kB>(a, sc, static_cast<hipStream_t>(stream)));
