@@ -6,7 +6,10 @@ block absmax, re-quantization (Sec. IV of the paper), on inputs that are already
 HBM.  Default workload: one flat fp32 tensor of 10^9 parameters, B = 2048 (the configuration
 the bandwidth target is stated on).  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1b|1m] [--no-cpu]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1b|...] [--no-cpu]
+
+Other workloads (not the headline line): 1m (configuration 1), c2, c3, c5 (multi-tensor
+configurations 2, 3, 5), sgd1b, quant1b, dequant1b (the other kernels at 1e9 elements).
 """
 from __future__ import annotations
 
@@ -27,6 +30,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 WORKLOADS = {
     "1b": dict(n=1_000_000_000, B=2048, name="config4: flat fp32 tensor, 1e9 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "1m": dict(n=1 << 20, B=2048, name="config1: flat fp32 tensor, 2^20 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
+    "sgd1b": dict(n=1_000_000_000, B=2048, name="flat fp32 tensor, 1e9 params, 8-bit SGD momentum, B=2048, grads N(0,1e-3)"),
 }
 
 
@@ -83,17 +87,113 @@ def cpu_baseline(w_dev, g_dev, B: int, sample: int, steps: int):
                        "block ranges split over %d threads" % (n, steps, cores))
 
 
+def build_workload(name, torch, q8opt, dev):
+    """Returns (description, params per step, algorithmic bytes per step, kernel name, step function,
+    (w, g, B) for the cpu_baseline leg or None)."""
+    from paper_2412_01195_amd import synth
+    tab_s = q8opt.upload_qtable(q8opt.build_qtable(q8opt.build_codebook(True)))
+    tab_u = q8opt.upload_qtable(q8opt.build_qtable(q8opt.build_codebook(False)))
+    gen = torch.Generator(device=dev); gen.manual_seed(4)
+    keep = [tab_s, tab_u]
+
+    def state8(n, B, adam=True):
+        nb = -(-n // B)
+        st = dict(m_q=torch.full((n,), 127, dtype=torch.uint8, device=dev), N_m=torch.zeros(nb, device=dev))
+        if adam:
+            st.update(r_q=torch.zeros(n, dtype=torch.uint8, device=dev), N_r=torch.zeros(nb, device=dev))
+        return st
+
+    if name in ("1b", "1m", "sgd1b"):
+        wl = WORKLOADS[name]
+        n, B = wl["n"], wl["B"]
+        w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
+        g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen)
+        adam = name != "sgd1b"
+        st = state8(n, B, adam)
+        t = [0]
+        if adam:
+            def step():
+                t[0] += 1
+                q8opt.adam8bit_step(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], tab_s, tab_u, B, **ADAM, t=t[0])
+            return wl["name"], n, algorithmic_bytes(n, B), "adam8_kernel<%d>" % B, step, (w, g, B), keep
+        def step():
+            q8opt.sgd8bit_step(w, g, st["m_q"], st["N_m"], tab_s, B, 0.1, 0.9, 1e-4)
+        return wl["name"], n, 14 * n + 8 * (-(-n // B)), "sgd8_kernel<%d>" % B, step, None, keep
+    if name in ("quant1b", "dequant1b"):
+        n, B = 1_000_000_000, 2048
+        nb = -(-n // B)
+        T = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen)
+        TQ = torch.empty(n, dtype=torch.uint8, device=dev); N = torch.empty(nb, device=dev)
+        q8opt.quantize_blockwise(tab_s, T, B, TQ, N)
+        if name == "quant1b":
+            return ("stand-alone block-wise quantization (Eq. quant1-2), 1e9 fp32 values, B=2048", n, 5 * n + 4 * nb,
+                    "quantize_kernel<2048>", lambda: q8opt.quantize_blockwise(tab_s, T, B, TQ, N), None, keep)
+        return ("stand-alone dequantization (Eq. quant3), 1e9 codes, B=2048", n, 5 * n + 4 * nb,
+                "dequantize_kernel", lambda: q8opt.dequantize_blockwise(tab_s, TQ, N, B, T), None, keep)
+    # multi-tensor lists
+    if name == "c5":
+        B, adam, min8 = 256, True, 0
+        sizes = [1_562_500] * 64
+        stds = [synth.heavy_tail_scale(5, i) for i in range(64)]
+        desc = "config5: 64 tensors x 1 562 500 params, 8-bit Adam, B=256, Student-t(3) grads scaled 1e-6..1e-1 per tensor"
+    elif name == "c2":
+        B, adam, min8 = 2048, False, 0
+        specs = synth.resnet34_specs(); sizes = [s.numel for s in specs]
+        stds = [synth.fan_in_std(s, 1e-2) for s in specs]
+        desc = "config2: ResNet34-shaped list, 111 tensors, 8 168 800 params, 8-bit SGD momentum, B=2048"
+    else:
+        B, adam, min8 = 2048, True, 4096
+        specs = synth.resnet293_specs(); sizes = [s.numel for s in specs]
+        stds = [1e-3] * len(sizes)
+        desc = "config3: ResNet293-shaped list, 891 tensors, 30 160 480 params, 8-bit Adam (fp32 states under 4096 elements), B=2048"
+    tensors, alg = [], 0
+    for n, sd in zip(sizes, stds):
+        w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
+        if name == "c5":
+            z = torch.randn(n, device=dev, generator=gen)
+            chi = torch.randn(3, n, device=dev, generator=gen).pow_(2).sum(0).div_(3.0).sqrt_()
+            g = z.div_(chi).mul_(sd)
+        else:
+            g = torch.empty(n, device=dev).normal_(0.0, sd, generator=gen)
+        t = dict(w=w, g=g)
+        nb = -(-n // B)
+        if n >= min8:
+            t.update(state8(n, B, adam))
+            alg += (16 * n + 16 * nb) if adam else (14 * n + 8 * nb)
+        else:
+            t["m_f32"] = torch.zeros(n, device=dev)
+            if adam:
+                t["r_f32"] = torch.zeros(n, device=dev)
+            alg += (32 if adam else 20) * n
+        tensors.append(t)
+    plan = q8opt.Plan(tensors, B)
+    keep += [tensors, plan]
+    tt = [0]
+    if adam:
+        def step():
+            tt[0] += 1
+            plan.multi_adam8bit_step(tab_s, tab_u, **ADAM, t=tt[0])
+        kern = "adam8_kernel<%d>" % B
+    else:
+        def step():
+            plan.multi_sgd8bit_step(tab_s, 0.1, 0.9, 1e-4)
+        kern = "sgd8_kernel<%d>" % B
+    return desc, sum(sizes), alg, kern, step, None, keep
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="1b", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="1b",
+                    choices=["1b", "1m", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5"],
+                    help="1b (default) = configuration 4, the one the headline metric is quoted on")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="after timing, run one plain elementwise copy of the fp32 weights (4n bytes read, "
-                         "4n written) so that counter runs can scale FETCH_SIZE / WRITE_SIZE")
+                    help="after timing, run one plain elementwise copy of a 1e9-float tensor (4e9 bytes read, "
+                         "4e9 written) so that counter runs can scale FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (no sharding, no collectives); --gpus must be 1", file=sys.stderr)
@@ -105,26 +205,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
     q8opt.lib()
-    wl = WORKLOADS[args.workload]
-    n, B = wl["n"], wl["B"]
-    nb = -(-n // B)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    tab_s = q8opt.upload_qtable(q8opt.build_qtable(q8opt.build_codebook(True)))
-    tab_u = q8opt.upload_qtable(q8opt.build_qtable(q8opt.build_codebook(False)))
-    gen = torch.Generator(device=dev); gen.manual_seed(4)
-    w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
-    g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen)
-    m_q = torch.full((n,), 127, dtype=torch.uint8, device=dev)
-    r_q = torch.zeros(n, dtype=torch.uint8, device=dev)
-    N_m = torch.zeros(nb, device=dev); N_r = torch.zeros(nb, device=dev)
-
-    t = 0
-
-    def step():
-        nonlocal t
-        t += 1
-        q8opt.adam8bit_step(w, g, m_q, r_q, N_m, N_r, tab_s, tab_u, B, **ADAM, t=t)
+    desc, nparams, alg, kernel, step, cpu_args, keep = build_workload(args.workload, torch, q8opt, dev)
 
     for _ in range(args.warmup):
         step()
@@ -139,34 +222,35 @@ def main():
     avg_kern_s = sum(kern_ms) / len(kern_ms) / 1e3
 
     if args.calibrate_copy:
-        scratch = torch.empty_like(g)
-        torch.mul(g, 1.0, out=scratch)
+        src = torch.zeros(1_000_000_000, device=dev)
+        dst = torch.empty_like(src)
+        torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
-        del scratch
+        del src, dst
 
-    alg = algorithmic_bytes(n, B)
     achieved = alg / avg_kern_s / 1e9
+    headline = args.workload in ("1b", "1m")
     out = {
-        "metric": "fused 8-bit Adam step: params/sec (achieved HBM GB/s in roofline)",
-        "value": n * args.steps / elapsed,
+        "metric": "fused 8-bit Adam step: params/sec (achieved HBM GB/s in roofline)" if headline
+                  else "%s: params/sec (achieved HBM GB/s in roofline)" % kernel,
+        "value": nparams * args.steps / elapsed,
         "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 update, u8 states", "data": "synthetic",
-        "config": {"workload": wl["name"], "params": n, "block_size": B, "optimizer": "adam8bit",
-                   "hyper": ADAM, "bytes_per_param": 16},
+        "config": {"workload": desc, "params": nparams, "hyper": ADAM if "adam" in kernel else None},
         "hbm_gbps": achieved, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(os.path.join(ROOT, "profiles", "adam8_kernel_1b_hbm_counters.md"))
                      if args.workload == "1b" else None,
-                     "kernel": "adam8_kernel<2048>", "kernel_ms_avg": avg_kern_s * 1e3,
+                     "kernel": kernel, "kernel_ms_avg": avg_kern_s * 1e3,
                      "kernel_ms_min": min(kern_ms), "kernel_ms_each": [round(x, 4) for x in kern_ms],
                      "algorithmic_bytes_per_launch": alg},
     }
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, g, B, args.cpu_sample, steps=2)
+    if not args.no_cpu and cpu_args is not None:
+        out["cpu_baseline"] = cpu_baseline(*cpu_args, args.cpu_sample, steps=2)
     print(json.dumps(out))
 
 
