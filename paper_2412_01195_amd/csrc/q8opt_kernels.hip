@@ -214,15 +214,43 @@ __device__ __forceinline__ float div_any(float a, float N)
 
 struct BlockNorm { float N, y, ylo; bool fast; };
 
+__device__ __forceinline__ bool norm_in_fast_range(uint32_t nbits)
+{
+    return (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
+}
+
+// Reciprocal data of one block maximum held per lane (used when lanes of a wave
+// belong to different blocks, B < 256).
 __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
 {
     BlockNorm b;
     b.N = __uint_as_float(nbits);
-    b.fast = (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
+    b.fast = norm_in_fast_range(nbits);
     b.y = b.fast ? 1.0f / b.N : 0.0f;
     const float e = __builtin_fmaf(-b.N, b.y, 1.0f);
     b.ylo = e * b.y;
     return b;
+}
+
+// Reciprocal data of K wave-uniform block maxima with ONE division sequence: the
+// K values are spread over lanes 0..K-1, divided there, and read back.
+template <int K>
+__device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm (&out)[K], int lane)
+{
+    int v = (int)nbits[0];
+#pragma unroll
+    for (int k = 1; k < K; ++k) v = (lane == k) ? (int)nbits[k] : v;
+    const float N = __int_as_float(v);
+    const float y = norm_in_fast_range((uint32_t)v) ? 1.0f / N : 0.0f;
+    const float e = __builtin_fmaf(-N, y, 1.0f);
+    const float ylo = e * y;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        out[k].N = __uint_as_float(nbits[k]);
+        out[k].fast = norm_in_fast_range(nbits[k]);
+        out[k].y = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y), k));
+        out[k].ylo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ylo), k));
+    }
 }
 
 // Correctly rounded square root for r == +0 or r >= 2^-100 (finite).  v_sqrt_f32
@@ -316,6 +344,32 @@ struct Shape {
     static constexpr int NBLK = kWaveRows / RPB;                        // block slots per lane
 };
 
+// Block maxima of NSTATE states x NBLK slots -> reciprocal data.
+template <int B, int NSTATE>
+__device__ __forceinline__ void norms_of(const uint32_t (&nbits)[NSTATE][Shape<B>::NBLK],
+                                         BlockNorm (&out)[NSTATE][Shape<B>::NBLK], int lane)
+{
+    using S = Shape<B>;
+    if (S::GROUP == 64) {
+        uint32_t flat[NSTATE * S::NBLK];
+        BlockNorm bn[NSTATE * S::NBLK];
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) flat[st * S::NBLK + k] = nbits[st][k];
+        make_norms<NSTATE * S::NBLK>(flat, bn, lane);
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) out[st][k] = bn[st * S::NBLK + k];
+    } else {
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) out[st][k] = make_norm(nbits[st][k]);
+    }
+}
+
 // LDS words for the exchange of wave maxima: [parity][state][wave].
 struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
 
@@ -358,18 +412,18 @@ __device__ __forceinline__ void idle_block_max()
 }
 
 // Quantize the 4 x 4 values of this lane (Eq. quant1, quant2) against the block
-// maxima `nbits` (bit patterns of N per block slot) and store codes and maxima.
+// maxima (with their reciprocal data, one entry per block slot) and store codes and maxima.
 // `base` is the first element of this wave, `part` its index inside the unit.
 template <int B, bool FULL, bool SECOND>
 __device__ __forceinline__ void requantize_store(const unsigned char* lds, float (&val)[kWaveRows][4],
-                                                 const uint32_t (&nbits)[Shape<B>::NBLK],
+                                                 const BlockNorm (&norms)[Shape<B>::NBLK],
                                                  gbyte* codes, gfloat* Nout,
                                                  int64_t n, int64_t base, int part, int lane)
 {
     using S = Shape<B>;
 #pragma unroll
     for (int s = 0; s < S::NBLK; ++s) {
-        const BlockNorm bn = make_norm(nbits[s]);
+        const BlockNorm bn = norms[s];
         const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
         if (B >= kRow) {
             if (part == 0 && lane == 0 && (FULL || row0 < n)) Nout[row0 / B] = bn.N;
@@ -561,8 +615,10 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
         }
     }
     reduce_block_max<B, 2>(amax, ex, parity, wave, lane);
-    requantize_store<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
-    requantize_store<B, FULL, true>(lds, wv, amax[1], r_q, (gfloat*)d.N_r, n, base, part, lane);
+    BlockNorm bn[2][S::NBLK];
+    norms_of<B, 2>(amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, gv, bn[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
+    requantize_store<B, FULL, true>(lds, wv, bn[1], r_q, (gfloat*)d.N_r, n, base, part, lane);
 }
 
 template <int B, bool FULL, bool WD>
@@ -611,7 +667,9 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
         if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
     }
     reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
-    requantize_store<B, FULL, false>(lds, gv, amax[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
+    BlockNorm bn[1][S::NBLK];
+    norms_of<B, 1>(amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, gv, bn[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
 }
 
 // Tensors that keep 32-bit states: same formulas, no quantization; one wave
@@ -675,7 +733,9 @@ __device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int
             amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(v[r][j]) & 0x7fffffffu);
     }
     reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
-    requantize_store<B, FULL, false>(lds, v, amax[0], TQ, N, n, base, part, lane);
+    BlockNorm bn[1][S::NBLK];
+    norms_of<B, 1>(amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, v, bn[0], TQ, N, n, base, part, lane);
 }
 
 // ---------------------------------------------------------------------------
@@ -905,11 +965,16 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void qu
     leave(sched);
 }
 
-// Eq. quant3.  A workgroup of 256 threads handles 8192 consecutive elements: 8
+// Eq. quant3.  A workgroup of 256 threads handles 4096 consecutive elements: 4
 // steps of 1024, one 4-element vector per thread and step; the block index of an
-// element is (index >> log2 B).  Launched flat (one workgroup per 8192 elements),
-// so the hardware dispatcher hands the chunks out in address order.
-constexpr int kDequantChunk = 8192;
+// element is (index >> log2 B).  Launched flat (one workgroup per 4096 elements),
+// so the hardware dispatcher hands the chunks out in address order (4 steps measured
+// best among 1, 2, 4, 8, 16).
+#ifndef Q8_DQ_STEPS
+#define Q8_DQ_STEPS 4
+#endif
+constexpr int kDequantSteps = Q8_DQ_STEPS;
+constexpr int kDequantChunk = 1024 * kDequantSteps;
 
 __global__ __launch_bounds__(256) void dequantize_kernel(const void* qtab, const uint8_t* TQ_, const float* N_,
                                                          int64_t n, int log2B, float* TD_)
@@ -921,18 +986,18 @@ __global__ __launch_bounds__(256) void dequantize_kernel(const void* qtab, const
     gcfloat* N = (gcfloat*)N_;
     gfloat* TD = (gfloat*)TD_;
     const int64_t chunk0 = (int64_t)blockIdx.x * kDequantChunk;
-    uint32_t c[8];
-    float Nb[8];
-    int cnt[8];
+    uint32_t c[kDequantSteps];
+    float Nb[kDequantSteps];
+    int cnt[kDequantSteps];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < kDequantSteps; ++i) {
         const int64_t e0 = chunk0 + i * 1024 + threadIdx.x * 4;
         cnt[i] = lane_count(n, e0);
         c[i] = cnt[i] > 0 ? load4b(TQ + e0, cnt[i]) : 0u;
         Nb[i] = cnt[i] > 0 ? N[e0 >> log2B] : 0.0f;       // B >= 64 is a multiple of 4: one block per vector
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < kDequantSteps; ++i) {
         const int64_t e0 = chunk0 + i * 1024 + threadIdx.x * 4;
         float out[4];
 #pragma unroll
