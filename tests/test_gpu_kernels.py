@@ -197,3 +197,52 @@ def test_runs_on_the_callers_stream(q8, tabs):
     s.synchronize()
     H.oracle_adam8(w_ref, g, st, B)
     H.assert_state_equal("side stream", d, st, w, w_ref)
+
+
+def test_concurrent_launches_on_two_streams(q8, tabs):
+    """Launches that overlap on different streams use different scheduler slots: two
+    independent tensors stepped concurrently for several steps still match the oracle, and
+    a later launch finds every slot left clean."""
+    n, B = (1 << 21) + 777, 2048
+    hosts, devs = [], []
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for k in range(2):
+        w_ref = synth.uniform_weights(500 + k, 0, n)
+        st = H.zero_state(n, B)
+        with torch.cuda.stream(streams[k]):
+            devs.append((dev(w_ref), {kk: dev(v) for kk, v in st.items()}))
+        hosts.append((w_ref, st))
+    for t in range(1, 6):
+        gs = [synth.normal_grad(500 + k, 0, t, n, 1e-3) for k in range(2)]
+        for k in range(2):
+            with torch.cuda.stream(streams[k]):
+                w, d = devs[k]
+                q8.adam8bit_step(w, dev(gs[k]), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B,
+                                 **H.ADAM, t=t)
+        for k in range(2):
+            H.oracle_adam8(hosts[k][0], gs[k], hosts[k][1], B, t=t)
+    torch.cuda.synchronize()
+    for k in range(2):
+        H.assert_state_equal("stream %d" % k, devs[k][1], hosts[k][1], devs[k][0], hosts[k][0])
+    # more launches than there are scheduler slots, back to back on one stream
+    w, d = devs[0]
+    w_ref, st = hosts[0]
+    g = synth.normal_grad(502, 0, 1, n, 1e-3); gd = dev(g)
+    for t in range(6, 6 + 70):
+        q8.adam8bit_step(w, gd, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        H.oracle_adam8(w_ref, g, st, B, t=t)
+    H.assert_state_equal("after 70 more launches", d, st, w, w_ref)
+
+
+def test_repeated_runs_are_bitwise_deterministic(q8, tabs):
+    n, B = 3_000_001, 256
+    w0 = synth.uniform_weights(600, 0, n); g = synth.normal_grad(600, 0, 1, n, 1e-3)
+    outs = []
+    for _ in range(2):
+        w = dev(w0); gd = dev(g)
+        d = {k: dev(v) for k, v in H.zero_state(n, B).items()}
+        for t in range(1, 4):
+            q8.adam8bit_step(w, gd, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        outs.append([w.cpu().numpy()] + [d[k].cpu().numpy() for k in sorted(d)])
+    for a, b in zip(*outs):
+        assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
