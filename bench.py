@@ -30,6 +30,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 WORKLOADS = {
     "1b": dict(n=1_000_000_000, B=2048, name="config4: flat fp32 tensor, 1e9 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "1m": dict(n=1 << 20, B=2048, name="config1: flat fp32 tensor, 2^20 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
+    "1b256": dict(n=1_000_000_000, B=256, name="flat fp32 tensor, 1e9 params, 8-bit Adam, B=256, grads N(0,1e-3)"),
+    "100m": dict(n=100_000_000, B=2048, name="flat fp32 tensor, 1e8 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "sgd1b": dict(n=1_000_000_000, B=2048, name="flat fp32 tensor, 1e9 params, 8-bit SGD momentum, B=2048, grads N(0,1e-3)"),
 }
 
@@ -103,7 +105,7 @@ def build_workload(name, torch, q8opt, dev):
             st.update(r_q=torch.zeros(n, dtype=torch.uint8, device=dev), N_r=torch.zeros(nb, device=dev))
         return st
 
-    if name in ("1b", "1m", "sgd1b"):
+    if name in ("1b", "1m", "sgd1b", "1b256", "100m"):
         wl = WORKLOADS[name]
         n, B = wl["n"], wl["B"]
         w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
@@ -187,8 +189,10 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="1b",
-                    choices=["1b", "1m", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5"],
+                    choices=["1b", "1m", "1b256", "100m", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5"],
                     help="1b (default) = configuration 4, the one the headline metric is quoted on")
+    ap.add_argument("--block-size", type=int, default=0,
+                    help="override the block size B of a flat workload (block-size sweep; not the headline line)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -207,6 +211,12 @@ def main():
     q8opt.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.block_size:
+        if args.workload not in WORKLOADS:
+            print("bench.py: --block-size applies to the flat workloads only", file=sys.stderr)
+            sys.exit(2)
+        WORKLOADS[args.workload] = dict(WORKLOADS[args.workload], B=args.block_size,
+                                        name=WORKLOADS[args.workload]["name"] + " [B overridden to %d]" % args.block_size)
     desc, nparams, alg, kernel, step, cpu_args, keep = build_workload(args.workload, torch, q8opt, dev)
 
     for _ in range(args.warmup):
@@ -229,7 +239,7 @@ def main():
         del src, dst
 
     achieved = alg / avg_kern_s / 1e9
-    headline = args.workload in ("1b", "1m")
+    headline = args.workload in ("1b", "1m") and not args.block_size
     out = {
         "metric": "fused 8-bit Adam step: params/sec (achieved HBM GB/s in roofline)" if headline
                   else "%s: params/sec (achieved HBM GB/s in roofline)" % kernel,

@@ -84,6 +84,30 @@ def resnet293_specs() -> List[TensorSpec]:
     return specs
 
 
+def df_resnet_specs(blocks=(3, 8, 48, 3)) -> List[TensorSpec]:
+    """Depth-first bottleneck backbone in its reversible form (Sec. III-C, table of
+    DF-RevNet66): per stage with half-width c in (24, 48, 96, 192), `blocks[s]` pairs of
+    residual functions F and G, each a 1x1 conv c->4c with BN, a depth-wise 3x3 conv on 4c
+    channels and a 1x1 conv 4c->c; 3x3 down-sampling convs between stages; a 7680x256
+    embedding layer and the speaker head.  blocks=(2, 2, 4, 2) gives the 4.8 M-parameter
+    DF-RevNet66, the default the deepest variant."""
+    specs = [_conv("conv1", 48, 1, 3)] + _bn("bn1", 48) + [_conv("conv2", 48, 48, 3)] + _bn("bn2", 48)
+    widths = (24, 48, 96, 192)
+    for s, (c, nblk) in enumerate(zip(widths, blocks)):
+        for b in range(nblk):
+            for fn in ("F", "G"):
+                p = f"stage{s + 1}.{b}.{fn}"
+                specs.append(_conv(p + ".expand", 4 * c, c, 1)); specs += _bn(p + ".bn", 4 * c)
+                specs.append(TensorSpec(p + ".dconv", (4 * c, 1, 3, 3), 9))
+                specs.append(_conv(p + ".project", c, 4 * c, 1))
+        if s + 1 < len(widths):
+            specs.append(_conv(f"down{s + 1}", 4 * c, 2 * c, 3)); specs += _bn(f"down{s + 1}.bn", 4 * c)
+    specs.append(TensorSpec("embed.weight", (EMBED, 7680), 7680))
+    specs.append(TensorSpec("embed.bias", (EMBED,), 1))
+    specs.append(TensorSpec("head.weight", (SPEAKERS, EMBED), EMBED))
+    return specs
+
+
 def _rng(seed: int, *counter: int) -> np.random.Generator:
     key = np.zeros(2, dtype=np.uint64)
     key[0] = np.uint64(seed & 0xFFFFFFFFFFFFFFFF)

@@ -77,7 +77,7 @@ class FlatList:
             ts.append(t)
         return q8.Plan(ts, self.B)
 
-    def oracle_step(self, t, wd=0.0):
+    def oracle_step(self, t, wd=0.0, flags=0):
         qs, qu = H.codebooks()
         B = self.B
 
@@ -85,10 +85,10 @@ class FlatList:
             v = lambda k: self.view(self.h, i, k)
             if self.adam and self.is8[i]:
                 oracle.adam8bit_step(v("w"), v("g"), v("m_q"), v("r_q"), v("N_m"), v("N_r"), qs, qu, B,
-                                     H.ADAM["alpha"], H.ADAM["beta1"], H.ADAM["beta2"], H.ADAM["eps"], wd, t, 0)
+                                     H.ADAM["alpha"], H.ADAM["beta1"], H.ADAM["beta2"], H.ADAM["eps"], wd, t, flags)
             elif self.adam:
                 oracle.adam32_step(v("w"), v("g"), v("m_f32"), v("r_f32"), H.ADAM["alpha"], H.ADAM["beta1"],
-                                   H.ADAM["beta2"], H.ADAM["eps"], wd, t, 0)
+                                   H.ADAM["beta2"], H.ADAM["eps"], wd, t, flags)
             elif self.is8[i]:
                 oracle.sgd8bit_step(v("w"), v("g"), v("m_q"), v("N_m"), qs, B, H.SGD["alpha"], H.SGD["beta"], wd)
             else:
@@ -169,6 +169,51 @@ def test_config5_reduced_heavy_tail(q8, tabs):
         plan.multi_adam8bit_step(tabs[0], tabs[1], **H.ADAM, t=t)
         L.oracle_step(t)
         L.compare("config 5 (reduced) step %d" % t)
+    plan.destroy()
+
+
+def test_dfresnet_adamw_list(q8, tabs):
+    """Second architecture family of the paper (Sec. III-C, V): a DF-ResNet-shaped list in its
+    deepest reversible form (638 tensors, 14.1 M parameters, many depth-wise 3x3 and 1x1
+    tensors), trained as in the paper with AdamW (decoupled weight decay 0.05), here with the
+    bias-correction extension as well; tensors under 4096 elements keep 32-bit states."""
+    specs = synth.df_resnet_specs()
+    assert len(specs) == 638 and sum(s.numel for s in specs) == 14060656
+    small = synth.df_resnet_specs((2, 2, 4, 2))
+    assert sum(s.numel for s in small[:-1]) == 4801840          # the 4.8 M of the DF-RevNet66 table
+    L = FlatList([s.numel for s in specs], 2048, adam=True, min_8bit=4096)
+    for i, s in enumerate(specs):
+        L.view(L.h, i, "w")[:] = synth.uniform_weights(7, i, s.numel)
+    L.upload()
+    plan = L.plan(q8)
+    flags = q8.FLAG_DECOUPLED_WD | q8.FLAG_BIAS_CORRECTION
+    for t in range(1, 11):
+        for i, s in enumerate(specs):
+            L.view(L.h, i, "g")[:] = synth.normal_grad(7, i, t, s.numel, synth.fan_in_std(s, 1e-2))
+        L.d["g"].copy_(torch.from_numpy(L.h["g"]))
+        plan.multi_adam8bit_step(tabs[0], tabs[1], **H.ADAM, weight_decay=0.05, t=t, flags=flags)
+        L.oracle_step(t, wd=0.05, flags=flags)
+        L.compare("DF-ResNet list step %d" % t)
+    plan.destroy()
+
+
+@pytest.mark.parametrize("B", [64, 128, 256, 512, 1024, 2048, 4096])
+def test_block_size_sweep_mixed_list(q8, tabs, B):
+    """Every supported block size on a small list whose tensors start and end inside jobs,
+    units and blocks (sizes around multiples of 1024 and of B)."""
+    sizes = [1, 63, 1023, 1024, 1025, 4096, 4097, 5 * 4096 + 3, 3 * B, 3 * B + 1, 7 * B - 1, 100_003]
+    L = FlatList(sizes, B, adam=True)
+    for i, n in enumerate(sizes):
+        L.view(L.h, i, "w")[:] = synth.uniform_weights(8, i, n)
+    L.upload()
+    plan = L.plan(q8)
+    for t in range(1, 5):
+        for i, n in enumerate(sizes):
+            L.view(L.h, i, "g")[:] = synth.normal_grad(8, i, t, n, 1e-3)
+        L.d["g"].copy_(torch.from_numpy(L.h["g"]))
+        plan.multi_adam8bit_step(tabs[0], tabs[1], **H.ADAM, t=t)
+        L.oracle_step(t)
+        L.compare("B=%d step %d" % (B, t))
     plan.destroy()
 
 
