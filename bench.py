@@ -9,7 +9,8 @@ the bandwidth target is stated on).  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1b|...] [--no-cpu]
 
 Other workloads (not the headline line): 1m (configuration 1), c2, c3, c5 (multi-tensor
-configurations 2, 3, 5), sgd1b, quant1b, dequant1b (the other kernels at 1e9 elements).
+configurations 2, 3, 5), df (DF-ResNet-shaped list, AdamW), sgd1b, quant1b, dequant1b (the
+other kernels at 1e9 elements), 1b256 / 100m and --block-size (size and block-size effects).
 """
 from __future__ import annotations
 
@@ -143,6 +144,13 @@ def build_workload(name, torch, q8opt, dev):
         specs = synth.resnet34_specs(); sizes = [s.numel for s in specs]
         stds = [synth.fan_in_std(s, 1e-2) for s in specs]
         desc = "config2: ResNet34-shaped list, 111 tensors, 8 168 800 params, 8-bit SGD momentum, B=2048"
+    elif name == "df":
+        B, adam, min8 = 2048, True, 4096
+        specs = synth.df_resnet_specs(); sizes = [s.numel for s in specs]
+        stds = [synth.fan_in_std(s, 1e-2) for s in specs]
+        adamw = dict(weight_decay=0.05, flags=q8opt.FLAG_DECOUPLED_WD | q8opt.FLAG_BIAS_CORRECTION)
+        desc = ("DF-ResNet-shaped list (deepest reversible form), 638 tensors, 14 060 656 params, 8-bit AdamW "
+                "(decoupled wd 0.05, bias correction; fp32 states under 4096 elements), B=2048")
     else:
         B, adam, min8 = 2048, True, 4096
         specs = synth.resnet293_specs(); sizes = [s.numel for s in specs]
@@ -172,9 +180,11 @@ def build_workload(name, torch, q8opt, dev):
     keep += [tensors, plan]
     tt = [0]
     if adam:
+        extra = adamw if name == "df" else {}
+
         def step():
             tt[0] += 1
-            plan.multi_adam8bit_step(tab_s, tab_u, **ADAM, t=tt[0])
+            plan.multi_adam8bit_step(tab_s, tab_u, **ADAM, t=tt[0], **extra)
         kern = "adam8_kernel<%d>" % B
     else:
         def step():
@@ -189,7 +199,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="1b",
-                    choices=["1b", "1m", "1b256", "100m", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5"],
+                    choices=["1b", "1m", "1b256", "100m", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5", "df"],
                     help="1b (default) = configuration 4, the one the headline metric is quoted on")
     ap.add_argument("--block-size", type=int, default=0,
                     help="override the block size B of a flat workload (block-size sweep; not the headline line)")
