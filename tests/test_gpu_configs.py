@@ -302,6 +302,29 @@ def test_config4_one_billion_parameters_sampled(q8, tabs):
     print("config 4: %d sampled blocks, max parameter relative error %.3g" % (pick.size + 1, e))
 
 
+def test_more_than_2_31_elements(q8, tabs):
+    """One tensor of 2^31 + 2^20 + 777 elements (21.5 GB of device memory for w, g and both
+    states): element indices beyond 32 bits, sampled blocks on both sides of 2^31 and the
+    short last block."""
+    n, B = (1 << 31) + (1 << 20) + 777, 2048
+    gen = torch.Generator(device="cuda"); gen.manual_seed(31)
+    w = torch.empty(n, device="cuda").uniform_(-0.1, 0.1, generator=gen)
+    g = torch.empty(n, device="cuda")
+    d = device_state(n, B)
+    nb = oracle.nblocks(n, B)
+    pick, tail = sample_blocks(n, B, 600, 45)
+    edge = np.array([(1 << 31) // B - 2, (1 << 31) // B - 1, (1 << 31) // B, (1 << 31) // B + 1, nb - 3, nb - 2])
+    pick = np.unique(np.concatenate([pick, edge]))
+    assert tail == nb - 1 and n - tail * B == 777
+    so = SampledOracle(n, B, pick, tail, w)
+    for t in range(1, 3):
+        g.normal_(0.0, 1e-3, generator=gen)
+        so.step(g, t)
+        q8.adam8bit_step(w, g, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        so.compare("2^31+ elements step %d" % t, w, d)
+    check_block_properties("2^31+ elements", d, n, B)
+
+
 def heavy_tail_grad_device(n, B, scale, gen):
     z = torch.randn(n, device="cuda", generator=gen)
     chi = torch.randn(3, n, device="cuda", generator=gen).pow_(2).sum(0).div_(3.0).sqrt_()
