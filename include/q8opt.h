@@ -34,6 +34,18 @@
  *   - All arithmetic is IEEE binary32, one rounding per operation, no fused
  *     multiply-add in the update formulas; divisions and square roots are
  *     correctly rounded.
+ *   - Scheduling state: the step and quantize kernels hand out work through a
+ *     job counter in device memory.  The library keeps a ring of 64 such
+ *     counters per device (module data, nothing is allocated); every launch
+ *     takes the next one and its kernel leaves it zeroed.  Launches on one
+ *     stream, and up to 64 launches overlapping on different streams, are
+ *     therefore independent.  A launch captured into a HIP graph keeps the
+ *     counter it was given at capture time: replays of one graph are safe in
+ *     sequence; do not replay it concurrently with itself.  The device entry
+ *     points enqueue exactly one kernel (no memset, no copy), so they can be
+ *     captured once each kernel has been launched eagerly a first time (the
+ *     first launch queries occupancy and the counter address, which is not
+ *     allowed during capture).
  */
 #ifndef Q8OPT_H
 #define Q8OPT_H

@@ -246,3 +246,33 @@ def test_repeated_runs_are_bitwise_deterministic(q8, tabs):
         outs.append([w.cpu().numpy()] + [d[k].cpu().numpy() for k in sorted(d)])
     for a, b in zip(*outs):
         assert np.array_equal(a.view(np.uint8), b.view(np.uint8))
+
+
+def test_step_inside_a_captured_graph(q8, tabs):
+    """The step enqueues one kernel and nothing else (the scheduler counter resets itself,
+    no memset), so it can be captured into a HIP graph.  Each replay, with eager work and
+    synchronizations in between, is checked against the oracle."""
+    n, B = 300_000, 2048
+    w_ref = synth.uniform_weights(700, 0, n)
+    st = H.zero_state(n, B)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    g_dev = torch.zeros(n, device="cuda")
+    g0 = synth.normal_grad(700, 0, 0, n, 1e-3)
+    g_dev.copy_(dev(g0))
+    # eager warm-up on a side stream (fills the library's per-kernel caches), as torch requires
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        q8.adam8bit_step(w, g_dev, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM)
+    torch.cuda.current_stream().wait_stream(s)
+    H.oracle_adam8(w_ref, g0, st, B)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        q8.adam8bit_step(w, g_dev, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM)
+    for t in range(1, 6):
+        g = synth.normal_grad(700, 0, t, n, 1e-3)
+        g_dev.copy_(dev(g))                       # eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        H.oracle_adam8(w_ref, g, st, B)
+        H.assert_state_equal("replay %d" % t, d, st, w, w_ref)
