@@ -1013,7 +1013,6 @@ bool valid_block(int B) { return B >= 64 && B <= 4096 && (B & (B - 1)) == 0; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 int ilog2(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
 int unit_elems(int B) { return B > 1024 ? B : 1024; }                 // Shape<B>::UNIT
-int units_per_job(int B) { return kWavesPerWg / (unit_elems(B) / 1024); }   // Shape<B>::UPJ
 
 // Job counters of the dynamic scheduler: a ring of slots in device memory that
 // launches use in turn.  A kernel leaves its slot zeroed, so consecutive launches
