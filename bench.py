@@ -203,6 +203,8 @@ def main():
                     help="1b (default) = configuration 4, the one the headline metric is quoted on")
     ap.add_argument("--block-size", type=int, default=0,
                     help="override the block size B of a flat workload (block-size sweep; not the headline line)")
+    ap.add_argument("--params", type=int, default=0,
+                    help="override the number of parameters of a flat workload (size sweep; not the headline line)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -227,6 +229,12 @@ def main():
             sys.exit(2)
         WORKLOADS[args.workload] = dict(WORKLOADS[args.workload], B=args.block_size,
                                         name=WORKLOADS[args.workload]["name"] + " [B overridden to %d]" % args.block_size)
+    if args.params:
+        if args.workload not in WORKLOADS:
+            print("bench.py: --params applies to the flat workloads only", file=sys.stderr)
+            sys.exit(2)
+        WORKLOADS[args.workload] = dict(WORKLOADS[args.workload], n=args.params,
+                                        name=WORKLOADS[args.workload]["name"] + " [size overridden to %d]" % args.params)
     desc, nparams, alg, kernel, step, cpu_args, keep = build_workload(args.workload, torch, q8opt, dev)
 
     for _ in range(args.warmup):
@@ -249,7 +257,7 @@ def main():
         del src, dst
 
     achieved = alg / avg_kern_s / 1e9
-    headline = args.workload in ("1b", "1m") and not args.block_size
+    headline = args.workload in ("1b", "1m") and not args.block_size and not args.params
     out = {
         "metric": "fused 8-bit Adam step: params/sec (achieved HBM GB/s in roofline)" if headline
                   else "%s: params/sec (achieved HBM GB/s in roofline)" % kernel,
