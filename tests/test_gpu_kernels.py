@@ -276,3 +276,47 @@ def test_step_inside_a_captured_graph(q8, tabs):
         torch.cuda.synchronize()
         H.oracle_adam8(w_ref, g, st, B)
         H.assert_state_equal("replay %d" % t, d, st, w, w_ref)
+
+
+def test_checkpoint_resume_and_fp32_state_import(q8, tabs):
+    """The optimizer state is exactly {codes, absmax} in caller-owned buffers: a snapshot
+    restored into fresh buffers continues bit-identically.  An fp32 state (e.g. from a 32-bit
+    checkpoint) is imported with q8_quantize_blockwise and then stepped in 8 bits, matching
+    the oracle doing the same; exporting with q8_dequantize_blockwise matches too."""
+    n, B = 50_000, 2048
+    qs, qu = H.codebooks()
+    w0 = synth.uniform_weights(800, 0, n)
+    grads = [synth.normal_grad(800, 0, t, n, 1e-3) for t in range(1, 6)]
+    w = dev(w0); d = {k: dev(v) for k, v in H.zero_state(n, B).items()}
+    for t in range(1, 4):
+        q8.adam8bit_step(w, dev(grads[t - 1]), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+    snap_w = w.cpu().numpy().copy(); snap = {k: v.cpu().numpy().copy() for k, v in d.items()}
+    for t in range(4, 6):
+        q8.adam8bit_step(w, dev(grads[t - 1]), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+    w2 = dev(snap_w); d2 = {k: dev(v) for k, v in snap.items()}
+    for t in range(4, 6):
+        q8.adam8bit_step(w2, dev(grads[t - 1]), d2["m_q"], d2["r_q"], d2["N_m"], d2["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w2.cpu().numpy().view(np.uint32))
+    for k in d:
+        assert np.array_equal(d[k].cpu().numpy().view(np.uint8), d2[k].cpu().numpy().view(np.uint8)), k
+    # import of a 32-bit state
+    wr = w0.copy(); m32 = np.zeros(n, np.float32); r32 = np.zeros(n, np.float32)
+    for t in range(1, 4):
+        oracle.adam32_step(wr, grads[t - 1], m32, r32, **H.ADAM, t=t)
+    nb = oracle.nblocks(n, B)
+    mq = torch.empty(n, dtype=torch.uint8, device="cuda"); rq = torch.empty(n, dtype=torch.uint8, device="cuda")
+    Nm = torch.empty(nb, device="cuda"); Nr = torch.empty(nb, device="cuda")
+    q8.quantize_blockwise(tabs[0], dev(m32), B, mq, Nm)
+    q8.quantize_blockwise(tabs[1], dev(r32), B, rq, Nr)
+    st = dict(zip(("m_q", "N_m"), oracle.quantize_blockwise(qs, m32, B)))
+    st.update(zip(("r_q", "N_r"), oracle.quantize_blockwise(qu, r32, B)))
+    wd_ = dev(wr); dd = dict(m_q=mq, r_q=rq, N_m=Nm, N_r=Nr)
+    H.assert_state_equal("import", dd, st, wd_, wr)
+    for t in range(4, 6):
+        q8.adam8bit_step(wd_, dev(grads[t - 1]), mq, rq, Nm, Nr, tabs[0], tabs[1], B, **H.ADAM, t=t)
+        H.oracle_adam8(wr, grads[t - 1], st, B, t=t)
+        H.assert_state_equal("after import, step %d" % t, dd, st, wd_, wr)
+    out = torch.empty(n, device="cuda")
+    q8.dequantize_blockwise(tabs[0], mq, Nm, B, out)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32),
+                          oracle.dequantize_blockwise(qs, st["m_q"], st["N_m"], B).view(np.uint32))
