@@ -350,3 +350,78 @@ int oracle_sgd8bit_step(float *w, const float *g, uint8_t *m_q, float *N_m,
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------- */
+/* Extension outside the paper: weights and gradients stored as bfloat16      */
+/* (the upper 16 bits of a binary32: 1 sign, 8 exponent, 7 fraction bits).    */
+/* A stored value is widened exactly, the step runs in binary32 exactly as    */
+/* above, and the new weight is rounded to nearest-even bfloat16.  The 8-bit  */
+/* states and their block maxima are unaffected by the storage type.          */
+/* ------------------------------------------------------------------------- */
+float oracle_bf16_to_f32(uint16_t h)
+{
+    union { uint32_t u; float f; } v;
+    v.u = (uint32_t)h << 16;
+    return v.f;
+}
+
+/* Round to nearest, ties to the even 16-bit pattern: the 16 discarded bits    */
+/* are compared with one half (0x8000).  Overflow carries into the exponent   */
+/* and ends at infinity, as IEEE rounding requires; NaN stays NaN (quiet).    */
+uint16_t oracle_f32_to_bf16(float f)
+{
+    union { uint32_t u; float f; } v;
+    v.f = f;
+    uint32_t hi = v.u >> 16, lo = v.u & 0xffffu;
+    if ((v.u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)(hi | 0x0040u);
+    if (lo > 0x8000u || (lo == 0x8000u && (hi & 1u)))
+        hi += 1;
+    return (uint16_t)hi;
+}
+
+int oracle_adam8bit_step_bf16(uint16_t *w, const uint16_t *g,
+                              uint8_t *m_q, uint8_t *r_q, float *N_m, float *N_r,
+                              const float *q_signed, const float *q_unsigned,
+                              int64_t n, int B,
+                              float alpha, float beta1, float beta2, float eps,
+                              float wd, int64_t t, int flags)
+{
+    static _Thread_local float mbuf[ORACLE_MAX_B], rbuf[ORACLE_MAX_B];
+    if (n < 0 || B <= 0 || B > ORACLE_MAX_B)
+        return -1;
+    adam_scalars s = adam_prepare(alpha, beta1, beta2, eps, wd, t, flags);
+    for (int64_t st = 0, b = 0; st < n; st += B, ++b) {
+        int64_t len = (n - st < B) ? n - st : B;
+        for (int64_t i = 0; i < len; ++i) {
+            float m_prev = q_signed[m_q[st + i]] * N_m[b];
+            float r_prev = q_unsigned[r_q[st + i]] * N_r[b];
+            float w32 = oracle_bf16_to_f32(w[st + i]);
+            adam_element(&s, &w32, oracle_bf16_to_f32(g[st + i]), m_prev, r_prev, &mbuf[i], &rbuf[i]);
+            w[st + i] = oracle_f32_to_bf16(w32);
+        }
+        quantize_block(q_signed, mbuf, len, m_q + st, N_m + b);
+        quantize_block(q_unsigned, rbuf, len, r_q + st, N_r + b);
+    }
+    return 0;
+}
+
+int oracle_sgd8bit_step_bf16(uint16_t *w, const uint16_t *g, uint8_t *m_q, float *N_m,
+                             const float *q_signed, int64_t n, int B,
+                             float alpha, float beta, float wd)
+{
+    static _Thread_local float mbuf[ORACLE_MAX_B];
+    if (n < 0 || B <= 0 || B > ORACLE_MAX_B)
+        return -1;
+    for (int64_t st = 0, b = 0; st < n; st += B, ++b) {
+        int64_t len = (n - st < B) ? n - st : B;
+        for (int64_t i = 0; i < len; ++i) {
+            float m_prev = q_signed[m_q[st + i]] * N_m[b];
+            float w32 = oracle_bf16_to_f32(w[st + i]);
+            sgd_element(alpha, beta, wd, &w32, oracle_bf16_to_f32(g[st + i]), m_prev, &mbuf[i]);
+            w[st + i] = oracle_f32_to_bf16(w32);
+        }
+        quantize_block(q_signed, mbuf, len, m_q + st, N_m + b);
+    }
+    return 0;
+}

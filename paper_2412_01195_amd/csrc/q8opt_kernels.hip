@@ -41,6 +41,8 @@
 #include <stdint.h>
 
 #include <atomic>
+#include <mutex>
+#include <new>
 
 #include "q8opt.h"
 #include "q8opt_internal.h"
@@ -1023,23 +1025,29 @@ __device__ Sched g_sched[kSchedSlots];
 
 struct DeviceInfo { int cus; Sched* sched; };
 
+// One record per device, filled on the first call with that device current
+// (every GPU holds its own copy of g_sched at its own address).  Host threads
+// may call the library concurrently.
+constexpr int kMaxDevices = 64;
+std::mutex g_dev_mutex;
+DeviceInfo g_dev[kMaxDevices];      // cus == 0: not asked yet
+
 q8_status device_info(DeviceInfo& out)
 {
-    static int cached_dev = -1;
-    static DeviceInfo cached{};
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return Q8_ELAUNCH;
-    if (dev != cached_dev) {
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Q8_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    DeviceInfo& di = g_dev[dev];
+    if (di.cus == 0) {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             return Q8_ELAUNCH;
         void* p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess || !p) return Q8_ELAUNCH;
-        cached.cus = cus;
-        cached.sched = static_cast<Sched*>(p);
-        cached_dev = dev;
+        di.sched = static_cast<Sched*>(p);
+        di.cus = cus;
     }
-    out = cached;
+    out = di;
     return Q8_OK;
 }
 
@@ -1051,21 +1059,22 @@ Sched* next_sched_slot(const DeviceInfo& di)
 
 // Persistent grid: enough workgroups to fill every CU to the kernel's
 // occupancy, never more than there are jobs.
-// `per_cu` caches the occupancy query of one kernel (0 = not asked yet).
+// `per_cu` caches the occupancy query of one kernel (0 = not asked yet; the
+// answer is the same on every device of one model, so one cache serves all).
 template <typename K>
-q8_status grid_for(K kernel, int& per_cu, int64_t njobs, int& grid, Sched** slot)
+q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, int& grid, Sched** slot)
 {
     DeviceInfo di;
     q8_status st = device_info(di);
     if (st != Q8_OK) return st;
-    if (per_cu <= 0) {
-        int v = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&v, kernel, kWgThreads, 0) != hipSuccess || v <= 0)
+    int occ = per_cu.load(std::memory_order_relaxed);
+    if (occ <= 0) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, kWgThreads, 0) != hipSuccess || occ <= 0)
             return Q8_ELAUNCH;
-        per_cu = v;
+        per_cu.store(occ, std::memory_order_relaxed);
     }
     int64_t want = njobs;
-    int64_t cap = (int64_t)di.cus * per_cu;
+    int64_t cap = (int64_t)di.cus * occ;
     grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
     *slot = next_sched_slot(di);
@@ -1124,7 +1133,7 @@ q8_status make_adam_scalars(float alpha, float beta1, float beta2, float eps, fl
 template <int B>
 q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 {
-    static int per_cu = 0;
+    static std::atomic<int> per_cu{0};
     int grid;
     q8_status st = grid_for(adam8_kernel<B>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
     if (st != Q8_OK) return st;
@@ -1135,7 +1144,7 @@ q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 template <int B>
 q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 {
-    static int per_cu = 0;
+    static std::atomic<int> per_cu{0};
     int grid;
     q8_status st = grid_for(sgd8_kernel<B>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
     if (st != Q8_OK) return st;
@@ -1147,7 +1156,7 @@ template <int B>
 q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* N, int64_t n, hipStream_t stream)
 {
     const int64_t nunits = (n + Shape<B>::UNIT - 1) / Shape<B>::UNIT;
-    static int per_cu = 0;
+    static std::atomic<int> per_cu{0};
     int grid;
     Sched* slot = nullptr;
     q8_status st = grid_for(quantize_kernel<B>, per_cu, (nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &slot);
