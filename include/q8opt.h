@@ -25,8 +25,9 @@
  *   - B is a power of two in [64, 4096].  A tensor of n elements has
  *     ceil(n / B) blocks; the last block may be short (it is quantized over
  *     its valid elements only).  n == 0 is a no-op.
- *   - fp32 tensors (w, g, T, TD) must be 16-byte aligned, code arrays and
- *     absmax arrays 4-byte aligned, qtables 16-byte aligned (else Q8_EALIGN).
+ *   - fp32 tensors (w, g, T, TD) must be 16-byte aligned, bfloat16 w and g
+ *     (the _bf16 entry points) 8-byte aligned, code arrays and absmax arrays
+ *     4-byte aligned, qtables 16-byte aligned (else Q8_EALIGN).
  *   - Inputs must be finite; results for NaN/Inf inputs are unspecified (no
  *     out-of-bounds access happens).
  *   - Zero-initialised optimizer state = every code equal to the code of 0.0
@@ -154,6 +155,26 @@ Q8_API q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, float* 
                           float alpha, float beta, float weight_decay, void* stream);
 
 /*
+ * Weights and gradients stored as bfloat16 (an extension; the paper keeps both
+ * in binary32).  bfloat16 = the upper 16 bits of a binary32, passed as uint16_t.
+ * Each stored w and g is widened exactly, the step runs in binary32 exactly as
+ * in the entry points above (same formulas, same 8-bit states and block maxima),
+ * and the new weight is rounded once, to nearest-even, back to bfloat16.  An
+ * update smaller than half a bfloat16 unit in the last place of its weight
+ * therefore leaves that weight unchanged; the states still advance.
+ * Arguments as above except for the element type of w (in place) and g.
+ */
+Q8_API q8_status q8_adam8bit_step_bf16(uint16_t* w, const uint16_t* g,
+                                uint8_t* m_q, uint8_t* r_q, float* N_m, float* N_r,
+                                const void* qtable_signed, const void* qtable_unsigned,
+                                int64_t n, int B,
+                                float alpha, float beta1, float beta2, float eps,
+                                float weight_decay, int64_t t, int flags, void* stream);
+Q8_API q8_status q8_sgd8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8_t* m_q, float* N_m,
+                               const void* qtable_signed, int64_t n, int B,
+                               float alpha, float beta, float weight_decay, void* stream);
+
+/*
  * Multi-tensor launch: one kernel launch updates a whole list of parameter
  * tensors (blocks never span tensors).  A tensor with m_f32 != NULL keeps
  * 32-bit states (m_f32, and r_f32 for Adam; same update formulas, no
@@ -162,11 +183,13 @@ Q8_API q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, float* 
  * above.  q8_plan_create copies the list into a device table it owns
  * (synchronous); the tensors themselves stay owned by the caller and must
  * outlive the plan's use.  r_q/N_r/r_f32 may be NULL for a plan that is only
- * used with the SGD entry point.
+ * used with the SGD entry point.  w and g of every tensor of a plan hold
+ * binary32 (q8_plan_create) or bfloat16 (q8_plan_create_bf16, semantics of the
+ * _bf16 steps above; the 32-bit states m_f32/r_f32 stay binary32).
  */
 typedef struct q8_tensor {
-    float*       w;
-    const float* g;
+    void*        w;
+    const void*  g;
     int64_t      n;
     uint8_t*     m_q;
     uint8_t*     r_q;
@@ -179,6 +202,7 @@ typedef struct q8_tensor {
 typedef struct q8_plan q8_plan;
 
 Q8_API q8_status q8_plan_create(const q8_tensor* list /* host */, int count, int B, q8_plan** out);
+Q8_API q8_status q8_plan_create_bf16(const q8_tensor* list /* host */, int count, int B, q8_plan** out);
 Q8_API q8_status q8_plan_destroy(q8_plan* plan);
 
 Q8_API q8_status q8_multi_adam8bit_step(q8_plan* plan,

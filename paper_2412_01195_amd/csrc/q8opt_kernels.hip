@@ -75,10 +75,17 @@ typedef Q8_GLOBAL const v4f gcfloat4;
 typedef Q8_GLOBAL uint32_t gu32;
 typedef Q8_GLOBAL const uint32_t gcu32;
 typedef Q8_GLOBAL const v4u gcuint4;
+typedef Q8_GLOBAL uint16_t gu16;
+typedef Q8_GLOBAL const uint16_t gcu16;
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef Q8_GLOBAL v2u gv2u;
+typedef Q8_GLOBAL const v2u gcv2u;
 
 struct TensorDesc {                       // device-side mirror of q8_tensor
-    float* w;
-    const float* g;
+    void* w;                              // float or bfloat16 elements: fixed by the kernel's WT
+    const void* g;
     uint8_t* m_q;
     uint8_t* r_q;
     float* N_m;
@@ -93,6 +100,7 @@ struct TileRef { int32_t tensor; int32_t tile; };
 struct AdamScalars {
     float beta1, beta2, omb1, omb2, eps, wd, alpha_t, isbc2, alpha_wd;
     int wd_mode;                          // 0 none, 1 coupled (g += wd*w), 2 decoupled
+    int fast_ok;                          // eps and isbc2 allow the short square root / division
 };
 struct SgdScalars { float alpha, beta, wd; };
 
@@ -255,12 +263,38 @@ __device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm
     }
 }
 
-// Correctly rounded square root for r == +0 or r >= 2^-100 (finite).  v_sqrt_f32
-// is within one ulp; the two neighbours are tested with fma residuals, which are
-// exact in this range: r - s_dn s <= 0 means sqrt(r) lies below the midpoint of
-// s_dn and s (the geometric mean of two neighbours is within a quarter ulp^2 of
-// their midpoint, closer than any binary32 r can come), likewise for s_up.
-constexpr uint32_t kSqrtFastMinBits = 0x0D800000u;   // 2^-100
+// Short forms of the square root and of the division in the Adam weight update,
+// used on rows where every new state lies in [kFastLo, kFastHi] (and the host has
+// found eps and the bias-correction factor within [0, 2^10] resp. [1, 2^10]); all
+// other rows take sqrtf and the general a / b.
+//
+// Square root: v_sqrt_f32 is within one ulp; the two neighbours are tested with fma
+// residuals, which are exact in this range: r - s_dn s <= 0 means sqrt(r) lies below
+// the midpoint of s_dn and s (the geometric mean of two neighbours is within a
+// quarter ulp^2 of their midpoint, closer than any binary32 r can come), likewise
+// for s_up.
+//
+// Division: for r in the range, d = fma(sqrt(r), c, eps) lies in [2^-40, 2^31] and
+// |m| / d in [2^-111, 2^80].  For such operands the compiler's correctly rounded
+// a / b -- v_div_scale, v_rcp, one reciprocal refinement, a product and two quotient
+// refinements, v_div_fmas, v_div_fixup -- scales nothing and fixes nothing up (no
+// operand or quotient is zero, subnormal or near the exponent limits, the exponents
+// differ by less than 96), so the same chain of fma without those three
+// instructions returns the same bits.
+constexpr float kFastLo = 0x1p-80f;
+constexpr float kFastHi = 0x1p40f;
+
+__device__ __forceinline__ float div_rn_inrange(float a, float b)
+{
+    float y = __builtin_amdgcn_rcpf(b);
+    const float e = __builtin_fmaf(-b, y, 1.0f);
+    y = __builtin_fmaf(e, y, y);
+    float q = a * y;
+    float r = __builtin_fmaf(-b, q, a);
+    q = __builtin_fmaf(r, y, q);
+    r = __builtin_fmaf(-b, q, a);
+    return __builtin_fmaf(r, y, q);
+}
 
 __device__ __forceinline__ float sqrt_rn_fast(float r)
 {
@@ -283,6 +317,18 @@ __device__ __forceinline__ int lane_count(int64_t n, int64_t e0)
 {
     int64_t left = n - e0;
     return left >= 4 ? 4 : (left <= 0 ? 0 : (int)left);
+}
+
+// Running maximum of |x| over a lane's elements, kept as the bit pattern of a
+// non-negative float (finite inputs: the order of such floats is the order of their
+// bit patterns).  Written as a float maximum so that it compiles to v_max3_f32 with
+// |.| source modifiers, two elements per instruction.
+__device__ __forceinline__ uint32_t absmax4(uint32_t acc, const float (&v)[4])
+{
+    float a = __uint_as_float(acc);
+    a = __builtin_fmaxf(__builtin_fmaxf(a, __builtin_fabsf(v[0])), __builtin_fabsf(v[1]));
+    a = __builtin_fmaxf(__builtin_fmaxf(a, __builtin_fabsf(v[2])), __builtin_fabsf(v[3]));
+    return __float_as_uint(a);
 }
 
 __device__ __forceinline__ void load4f(gcfloat* p, int cnt, float (&v)[4])
@@ -326,6 +372,49 @@ __device__ __forceinline__ void store4b(gbyte* p, int cnt, uint32_t v)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (j < cnt) p[j] = (uint8_t)(v >> (8 * j));
+    }
+}
+
+// Storage type WT of weights and gradients: float, or Bf16 (bfloat16 = the upper
+// half of a binary32).  Widening is exact; narrowing is the hardware's
+// round-to-nearest-even conversion (v_cvt_pk_bf16_f32), applied once to the new weight.
+struct Bf16 { uint16_t bits; };
+
+template <typename WT> struct Wide;
+template <> struct Wide<float> { typedef gfloat* ptr; typedef gcfloat* cptr; };
+template <> struct Wide<Bf16> { typedef gu16* ptr; typedef gcu16* cptr; };
+
+__device__ __forceinline__ void load4w(gcfloat* p, int cnt, float (&v)[4]) { load4f(p, cnt, v); }
+__device__ __forceinline__ void store4w(gfloat* p, int cnt, const float (&v)[4]) { store4f(p, cnt, v); }
+
+__device__ __forceinline__ void load4w(gcu16* p, int cnt, float (&v)[4])
+{
+    if (cnt == 4) {
+        const v2u t = __builtin_nontemporal_load((gcv2u*)p);
+        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (j < cnt) ? __uint_as_float((uint32_t)p[j] << 16) : 0.0f;
+    }
+}
+
+__device__ __forceinline__ uint32_t narrow2(float lo, float hi)
+{
+    const v2f x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, v2bf));
+}
+
+__device__ __forceinline__ void store4w(gu16* p, int cnt, const float (&v)[4])
+{
+    const uint32_t a = narrow2(v[0], v[1]), b = narrow2(v[2], v[3]);
+    if (cnt == 4) {
+        const v2u t = {a, b};
+        __builtin_nontemporal_store(t, (gv2u*)p);
+    } else {
+        if (cnt > 0) p[0] = (uint16_t)a;
+        if (cnt > 1) p[1] = (uint16_t)(a >> 16);
+        if (cnt > 2) p[2] = (uint16_t)b;
     }
 }
 
@@ -504,7 +593,7 @@ __device__ __forceinline__ void adam_states(const AdamScalars& s, float w, float
 }
 
 // Weight update of Eq. adam from the new 32-bit states.  FAST selects the short
-// square root, valid when the caller has checked r == 0 or r >= 2^-100.
+// square root and division, valid when the caller has checked the range of m and r.
 template <int WD, bool FAST>
 __device__ __forceinline__ float adam_weight(const AdamScalars& s, float w, float m, float r)
 {
@@ -512,7 +601,7 @@ __device__ __forceinline__ float adam_weight(const AdamScalars& s, float w, floa
     // without bias correction isbc2 == 1 and the fma is exactly root + eps; with it the
     // denominator is defined as this single fused operation
     const float d = __builtin_fmaf(root, s.isbc2, s.eps);
-    const float u = m / d;
+    const float u = FAST ? div_rn_inrange(m, d) : m / d;
     const float t6 = s.alpha_t * u;
     if (WD == 2) {
         float t7 = s.alpha_wd * w;
@@ -550,14 +639,14 @@ __device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float
 // ---------------------------------------------------------------------------
 // Wave tiles.  `base` = first element of this wave inside the tensor.
 // ---------------------------------------------------------------------------
-template <int B, bool FULL, int WD>
+template <int B, typename WT, bool FULL, int WD>
 __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
                                            Exchange* ex, int parity, const AdamScalars& sc, int wave, int lane)
 {
     using S = Shape<B>;
     const int64_t n = d.n;
-    gfloat* w = (gfloat*)d.w;
-    gcfloat* g = (gcfloat*)d.g;
+    typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
+    typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
     gbyte* m_q = (gbyte*)d.m_q;
     gbyte* r_q = (gbyte*)d.r_q;
     float wv[kWaveRows][4], gv[kWaveRows][4];
@@ -568,8 +657,8 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(w + e0, cnt, wv[r]);
-            load4f(g + e0, cnt, gv[r]);
+            load4w(w + e0, cnt, wv[r]);
+            load4w(g + e0, cnt, gv[r]);
             mq[r] = load4b(m_q + e0, cnt);
             rq[r] = load4b(r_q + e0, cnt);
         } else {
@@ -589,31 +678,38 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         float mnew[4], rnew[4];
-        uint32_t rmin = 0xffffffffu;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
             const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[r]);
             adam_states<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, mnew[j], rnew[j]);
-            rmin = min(rmin, __float_as_uint(rnew[j]));
         }
-        // one wave-uniform test per row: every r of the row is at least 2^-100 (rows that
-        // hold an exact zero or a tinier value take the general square root)
-        if (__builtin_amdgcn_ballot_w64(rmin < kSqrtFastMinBits) == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
+        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], mnew);
+        amax[1][r / S::RPB] = absmax4(amax[1][r / S::RPB], rnew);
+        // one wave-uniform test per row: every |m| and r of the row within [kFastLo, kFastHi]
+        // (the running maxima bound the row from above; a row that holds an exact zero,
+        // e.g. in a ragged tail, takes the general forms)
+        float lo = __builtin_fminf(__builtin_fminf(__builtin_fabsf(mnew[0]), __builtin_fabsf(mnew[1])), __builtin_fabsf(mnew[2]));
+        lo = __builtin_fminf(__builtin_fminf(lo, __builtin_fabsf(mnew[3])), rnew[0]);
+        lo = __builtin_fminf(__builtin_fminf(lo, rnew[1]), rnew[2]);
+        lo = __builtin_fminf(lo, rnew[3]);
+        const float hi = __builtin_fmaxf(__uint_as_float(amax[0][r / S::RPB]), __uint_as_float(amax[1][r / S::RPB]));
+        const bool general = !(lo >= kFastLo) || !(hi <= kFastHi) || !sc.fast_ok;
+        if (__builtin_amdgcn_ballot_w64(general) == 0) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, true>(sc, wv[r][j], mnew[j], rnew[j]);
         } else {
 #pragma unroll
             for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, false>(sc, wv[r][j], mnew[j], rnew[j]);
         }
-        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
+        if (FULL || cnt > 0) store4w(w + e0, cnt, wv[r]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
             gv[r][j] = mnew[j];
             wv[r][j] = rnew[j];
-            amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(mnew[j]) & 0x7fffffffu);
-            amax[1][r / S::RPB] = max(amax[1][r / S::RPB], __float_as_uint(rnew[j]));
         }
     }
     reduce_block_max<B, 2>(amax, ex, parity, wave, lane);
@@ -623,14 +719,14 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
     requantize_store<B, FULL, true>(lds, wv, bn[1], r_q, (gfloat*)d.N_r, n, base, part, lane);
 }
 
-template <int B, bool FULL, bool WD>
+template <int B, typename WT, bool FULL, bool WD>
 __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
                                           Exchange* ex, int parity, const SgdScalars& sc, int wave, int lane)
 {
     using S = Shape<B>;
     const int64_t n = d.n;
-    gfloat* w = (gfloat*)d.w;
-    gcfloat* g = (gcfloat*)d.g;
+    typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
+    typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
     gbyte* m_q = (gbyte*)d.m_q;
     float wv[kWaveRows][4], gv[kWaveRows][4];
     uint32_t mq[kWaveRows];
@@ -640,8 +736,8 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(w + e0, cnt, wv[r]);
-            load4f(g + e0, cnt, gv[r]);
+            load4w(w + e0, cnt, wv[r]);
+            load4w(g + e0, cnt, gv[r]);
             mq[r] = load4b(m_q + e0, cnt);
         } else {
 #pragma unroll
@@ -664,9 +760,9 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
             sgd_element<WD>(sc, wv[r][j], gv[r][j], m_prev, m_new);
             if (!FULL && j >= cnt) m_new = 0.0f;
             gv[r][j] = m_new;
-            amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(m_new) & 0x7fffffffu);
         }
-        if (FULL || cnt > 0) store4f(w + e0, cnt, wv[r]);
+        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], gv[r]);
+        if (FULL || cnt > 0) store4w(w + e0, cnt, wv[r]);
     }
     reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
     BlockNorm bn[1][S::NBLK];
@@ -676,13 +772,13 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
 
 // Tensors that keep 32-bit states: same formulas, no quantization; one wave
 // handles its 1024 elements.
-template <bool ADAM>
+template <typename WT, bool ADAM>
 __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, const AdamScalars& as,
                                          const SgdScalars& ss, int lane)
 {
     const int64_t n = d.n;
-    gfloat* w = (gfloat*)d.w;
-    gcfloat* g = (gcfloat*)d.g;
+    typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
+    typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
     gfloat* m = (gfloat*)d.m_f32;
     gfloat* rr = (gfloat*)d.r_f32;
     for (int r = 0; r < kWaveRows; ++r) {
@@ -690,8 +786,8 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, cons
         const int cnt = lane_count(n, e0);
         if (cnt == 0) continue;
         float wv[4], gv[4], mv[4], rv[4] = {0.f, 0.f, 0.f, 0.f};
-        load4f(w + e0, cnt, wv);
-        load4f(g + e0, cnt, gv);
+        load4w(w + e0, cnt, wv);
+        load4w(g + e0, cnt, gv);
         load4f(m + e0, cnt, mv);
         if (ADAM) load4f(rr + e0, cnt, rv);
 #pragma unroll
@@ -705,7 +801,7 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, cons
                 else sgd_element<false>(ss, wv[j], gv[j], mv[j], mv[j]);
             }
         }
-        store4f(w + e0, cnt, wv);
+        store4w(w + e0, cnt, wv);
         store4f(m + e0, cnt, mv);
         if (ADAM) store4f(rr + e0, cnt, rv);
     }
@@ -730,9 +826,7 @@ __device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            amax[0][r / S::RPB] = max(amax[0][r / S::RPB], __float_as_uint(v[r][j]) & 0x7fffffffu);
+        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], v[r]);
     }
     reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
     BlockNorm bn[1][S::NBLK];
@@ -812,8 +906,8 @@ __device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t u, int6
         unit_in_tensor = ref[1];
         Q8_CONSTANT const uint64_t* f = (Q8_CONSTANT const uint64_t*)(a.descs + ti);
         TensorDesc d;
-        d.w = (float*)f[0];
-        d.g = (const float*)f[1];
+        d.w = (void*)f[0];
+        d.g = (const void*)f[1];
         d.m_q = (uint8_t*)f[2];
         d.r_q = (uint8_t*)f[3];
         d.N_m = (float*)f[4];
@@ -837,7 +931,7 @@ struct Lds {
 constexpr int kStepSpan = 1;        // jobs per draw of the optimizer-step kernels
 constexpr int kQuantSpan = 4;       // the stand-alone quantizer does far less work per job
 
-template <int B, int WD>
+template <int B, typename WT, int WD>
 __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars& sc, Lds* lds)
 {
     using S = Shape<B>;
@@ -859,12 +953,12 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
                 const TensorDesc d = resolve(a, u, ut);
                 const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
                 if (d.m_f32) {
-                    f32_tile<true>(d, base, sc, none, lane);
+                    f32_tile<WT, true>(d, base, sc, none, lane);
                 } else if (base + kWaveElems <= d.n) {
-                    adam8_tile<B, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    adam8_tile<B, WT, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
                     done = true;
                 } else {
-                    adam8_tile<B, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    adam8_tile<B, WT, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
                     done = true;
                 }
             }
@@ -873,20 +967,20 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
     }
 }
 
-template <int B>
+template <int B, typename WT>
 __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     stage_second(lds.tab, a.qtab_u, threadIdx.x);
     __syncthreads();
-    if (sc.wd_mode == 0) adam8_walk<B, 0>(a, sc, &lds);
-    else if (sc.wd_mode == 1) adam8_walk<B, 1>(a, sc, &lds);
-    else adam8_walk<B, 2>(a, sc, &lds);
+    if (sc.wd_mode == 0) adam8_walk<B, WT, 0>(a, sc, &lds);
+    else if (sc.wd_mode == 1) adam8_walk<B, WT, 1>(a, sc, &lds);
+    else adam8_walk<B, WT, 2>(a, sc, &lds);
     leave(a.sched);
 }
 
-template <int B, bool WD>
+template <int B, typename WT, bool WD>
 __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& sc, Lds* lds)
 {
     using S = Shape<B>;
@@ -908,12 +1002,12 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
                 const TensorDesc d = resolve(a, u, ut);
                 const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
                 if (d.m_f32) {
-                    f32_tile<false>(d, base, none, sc, lane);
+                    f32_tile<WT, false>(d, base, none, sc, lane);
                 } else if (base + kWaveElems <= d.n) {
-                    sgd8_tile<B, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    sgd8_tile<B, WT, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
                     done = true;
                 } else {
-                    sgd8_tile<B, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    sgd8_tile<B, WT, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
                     done = true;
                 }
             }
@@ -922,14 +1016,14 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
     }
 }
 
-template <int B>
+template <int B, typename WT>
 __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     __syncthreads();
-    if (sc.wd != 0.0f) sgd8_walk<B, true>(a, sc, &lds);
-    else sgd8_walk<B, false>(a, sc, &lds);
+    if (sc.wd != 0.0f) sgd8_walk<B, WT, true>(a, sc, &lds);
+    else sgd8_walk<B, WT, false>(a, sc, &lds);
     leave(a.sched);
 }
 
@@ -1125,30 +1219,31 @@ q8_status make_adam_scalars(float alpha, float beta1, float beta2, float eps, fl
         s.alpha_t = (float)((double)alpha / bc1);
         s.isbc2 = (float)(1.0 / sqrt(bc2));
     }
+    s.fast_ok = (eps >= 0.0f && eps <= 1024.0f && s.isbc2 >= 1.0f && s.isbc2 <= 1024.0f) ? 1 : 0;
     s.alpha_wd = alpha * wd;
     s.wd_mode = (wd == 0.0f) ? 0 : ((flags & Q8_FLAG_DECOUPLED_WD) ? 2 : 1);
     return Q8_OK;
 }
 
-template <int B>
+template <int B, typename WT>
 q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 {
     static std::atomic<int> per_cu{0};
     int grid;
-    q8_status st = grid_for(adam8_kernel<B>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
+    q8_status st = grid_for(adam8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
     if (st != Q8_OK) return st;
-    hipLaunchKernelGGL(adam8_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
+    hipLaunchKernelGGL((adam8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
 }
 
-template <int B>
+template <int B, typename WT>
 q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 {
     static std::atomic<int> per_cu{0};
     int grid;
-    q8_status st = grid_for(sgd8_kernel<B>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
+    q8_status st = grid_for(sgd8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
     if (st != Q8_OK) return st;
-    hipLaunchKernelGGL(sgd8_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
+    hipLaunchKernelGGL((sgd8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
 }
 
@@ -1174,6 +1269,7 @@ struct q8_plan {
     int count;
     int B;
     bool has_r;        // every tensor carries second-state storage (usable with Adam)
+    bool bf16;         // w and g of every tensor hold bfloat16
 };
 
 extern "C" q8_status q8_quantize_blockwise(const void* qtable, const float* T, int64_t n, int B,
@@ -1203,10 +1299,16 @@ extern "C" q8_status q8_dequantize_blockwise(const void* qtable, const uint8_t* 
     return launch_status();
 }
 
-extern "C" q8_status q8_adam8bit_step(float* w, const float* g, uint8_t* m_q, uint8_t* r_q, float* N_m, float* N_r,
-                                      const void* qtable_signed, const void* qtable_unsigned, int64_t n, int B,
-                                      float alpha, float beta1, float beta2, float eps, float weight_decay,
-                                      int64_t t, int flags, void* stream)
+namespace {
+
+// w/g alignment: one lane vector = 4 elements of the storage type.
+template <typename WT> constexpr size_t wg_align() { return 4 * sizeof(WT); }
+
+template <typename WT>
+q8_status adam_step(void* w, const void* g, uint8_t* m_q, uint8_t* r_q, float* N_m, float* N_r,
+                    const void* qtable_signed, const void* qtable_unsigned, int64_t n, int B,
+                    float alpha, float beta1, float beta2, float eps, float weight_decay,
+                    int64_t t, int flags, void* stream)
 {
     if (n < 0) return Q8_EINVAL;
     if (!valid_block(B)) return Q8_EBLOCK;
@@ -1215,49 +1317,87 @@ extern "C" q8_status q8_adam8bit_step(float* w, const float* g, uint8_t* m_q, ui
     if (st != Q8_OK) return st;
     if (n == 0) return Q8_OK;
     if (!w || !g || !m_q || !r_q || !N_m || !N_r || !qtable_signed || !qtable_unsigned) return Q8_EINVAL;
-    if (!aligned(w, 16) || !aligned(g, 16) || !aligned(m_q, 4) || !aligned(r_q, 4) || !aligned(N_m, 4) ||
-        !aligned(N_r, 4) || !aligned(qtable_signed, 16) || !aligned(qtable_unsigned, 16))
+    if (!aligned(w, wg_align<WT>()) || !aligned(g, wg_align<WT>()) || !aligned(m_q, 4) || !aligned(r_q, 4) ||
+        !aligned(N_m, 4) || !aligned(N_r, 4) || !aligned(qtable_signed, 16) || !aligned(qtable_unsigned, 16))
         return Q8_EALIGN;
     StepArgs a{};
     a.single = TensorDesc{w, g, m_q, r_q, N_m, N_r, nullptr, nullptr, n};
     a.nunits = (n + unit_elems(B) - 1) / unit_elems(B);
     a.qtab_s = qtable_signed;
     a.qtab_u = qtable_unsigned;
-    Q8_DISPATCH_B(B, return launch_adam<kB>(a, sc, static_cast<hipStream_t>(stream)));
+    Q8_DISPATCH_B(B, return (launch_adam<kB, WT>(a, sc, static_cast<hipStream_t>(stream))));
     return Q8_OK;
 }
 
-extern "C" q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, float* N_m, const void* qtable_signed,
-                                     int64_t n, int B, float alpha, float beta, float weight_decay, void* stream)
+template <typename WT>
+q8_status sgd_step(void* w, const void* g, uint8_t* m_q, float* N_m, const void* qtable_signed,
+                   int64_t n, int B, float alpha, float beta, float weight_decay, void* stream)
 {
     if (n < 0) return Q8_EINVAL;
     if (!valid_block(B)) return Q8_EBLOCK;
     if (n == 0) return Q8_OK;
     if (!w || !g || !m_q || !N_m || !qtable_signed) return Q8_EINVAL;
-    if (!aligned(w, 16) || !aligned(g, 16) || !aligned(m_q, 4) || !aligned(N_m, 4) || !aligned(qtable_signed, 16))
+    if (!aligned(w, wg_align<WT>()) || !aligned(g, wg_align<WT>()) || !aligned(m_q, 4) || !aligned(N_m, 4) ||
+        !aligned(qtable_signed, 16))
         return Q8_EALIGN;
     StepArgs a{};
     a.single = TensorDesc{w, g, m_q, nullptr, N_m, nullptr, nullptr, nullptr, n};
     a.nunits = (n + unit_elems(B) - 1) / unit_elems(B);
     a.qtab_s = qtable_signed;
     SgdScalars sc{alpha, beta, weight_decay};
-    Q8_DISPATCH_B(B, return launch_sgd<kB>(a, sc, static_cast<hipStream_t>(stream)));
+    Q8_DISPATCH_B(B, return (launch_sgd<kB, WT>(a, sc, static_cast<hipStream_t>(stream))));
     return Q8_OK;
 }
 
-extern "C" q8_status q8_plan_create(const q8_tensor* list, int count, int B, q8_plan** out)
+}  // namespace
+
+extern "C" q8_status q8_adam8bit_step(float* w, const float* g, uint8_t* m_q, uint8_t* r_q, float* N_m, float* N_r,
+                                      const void* qtable_signed, const void* qtable_unsigned, int64_t n, int B,
+                                      float alpha, float beta1, float beta2, float eps, float weight_decay,
+                                      int64_t t, int flags, void* stream)
+{
+    return adam_step<float>(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, n, B, alpha, beta1, beta2, eps,
+                            weight_decay, t, flags, stream);
+}
+
+extern "C" q8_status q8_adam8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8_t* m_q, uint8_t* r_q, float* N_m,
+                                           float* N_r, const void* qtable_signed, const void* qtable_unsigned,
+                                           int64_t n, int B, float alpha, float beta1, float beta2, float eps,
+                                           float weight_decay, int64_t t, int flags, void* stream)
+{
+    return adam_step<Bf16>(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, n, B, alpha, beta1, beta2, eps,
+                           weight_decay, t, flags, stream);
+}
+
+extern "C" q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, float* N_m, const void* qtable_signed,
+                                     int64_t n, int B, float alpha, float beta, float weight_decay, void* stream)
+{
+    return sgd_step<float>(w, g, m_q, N_m, qtable_signed, n, B, alpha, beta, weight_decay, stream);
+}
+
+extern "C" q8_status q8_sgd8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8_t* m_q, float* N_m,
+                                          const void* qtable_signed, int64_t n, int B, float alpha, float beta,
+                                          float weight_decay, void* stream)
+{
+    return sgd_step<Bf16>(w, g, m_q, N_m, qtable_signed, n, B, alpha, beta, weight_decay, stream);
+}
+
+namespace {
+
+q8_status plan_create(const q8_tensor* list, int count, int B, bool bf16, q8_plan** out)
 {
     if (!out) return Q8_EINVAL;
     *out = nullptr;
     if (!list || count <= 0) return Q8_EINVAL;
     if (!valid_block(B)) return Q8_EBLOCK;
     const int64_t te = unit_elems(B);
+    const size_t wg_al = bf16 ? wg_align<Bf16>() : wg_align<float>();
     int64_t ntiles = 0;
     bool has_r = true;
     for (int i = 0; i < count; ++i) {
         const q8_tensor& t = list[i];
         if (t.n < 0 || !t.w || !t.g) return Q8_EINVAL;
-        if (!aligned(t.w, 16) || !aligned(t.g, 16)) return Q8_EALIGN;
+        if (!aligned(t.w, wg_al) || !aligned(t.g, wg_al)) return Q8_EALIGN;
         if (t.m_f32) {
             if (!aligned(t.m_f32, 16) || !aligned(t.r_f32, 16)) return Q8_EALIGN;
             if (!t.r_f32) has_r = false;
@@ -1302,8 +1442,21 @@ extern "C" q8_status q8_plan_create(const q8_tensor* list, int count, int B, q8_
     p->count = count;
     p->B = B;
     p->has_r = has_r;
+    p->bf16 = bf16;
     *out = p;
     return Q8_OK;
+}
+
+}  // namespace
+
+extern "C" q8_status q8_plan_create(const q8_tensor* list, int count, int B, q8_plan** out)
+{
+    return plan_create(list, count, B, false, out);
+}
+
+extern "C" q8_status q8_plan_create_bf16(const q8_tensor* list, int count, int B, q8_plan** out)
+{
+    return plan_create(list, count, B, true, out);
 }
 
 extern "C" q8_status q8_plan_destroy(q8_plan* plan)
@@ -1332,7 +1485,10 @@ extern "C" q8_status q8_multi_adam8bit_step(q8_plan* plan, const void* qtable_si
     a.nunits = plan->ntiles;
     a.qtab_s = qtable_signed;
     a.qtab_u = qtable_unsigned;
-    Q8_DISPATCH_B(plan->B, return launch_adam<kB>(a, sc, static_cast<hipStream_t>(stream)));
+    if (plan->bf16) {
+        Q8_DISPATCH_B(plan->B, return (launch_adam<kB, Bf16>(a, sc, static_cast<hipStream_t>(stream))));
+    }
+    Q8_DISPATCH_B(plan->B, return (launch_adam<kB, float>(a, sc, static_cast<hipStream_t>(stream))));
     return Q8_OK;
 }
 
@@ -1348,6 +1504,9 @@ extern "C" q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_sig
     a.nunits = plan->ntiles;
     a.qtab_s = qtable_signed;
     SgdScalars sc{alpha, beta, weight_decay};
-    Q8_DISPATCH_B(plan->B, return launch_sgd<kB>(a, sc, static_cast<hipStream_t>(stream)));
+    if (plan->bf16) {
+        Q8_DISPATCH_B(plan->B, return (launch_sgd<kB, Bf16>(a, sc, static_cast<hipStream_t>(stream))));
+    }
+    Q8_DISPATCH_B(plan->B, return (launch_sgd<kB, float>(a, sc, static_cast<hipStream_t>(stream))));
     return Q8_OK;
 }

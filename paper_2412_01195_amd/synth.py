@@ -153,3 +153,10 @@ def heavy_tail_grad(seed: int, tensor: int, step: int, n: int, scale: float, blo
 
 def fan_in_std(spec: TensorSpec, base: float) -> float:
     return base / math.sqrt(spec.fan_in)
+
+
+def bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Inputs for the bfloat16-storage entry points: the upper 16 bits of each float32
+    (plain truncation -- this only manufactures representable test inputs)."""
+    x = np.ascontiguousarray(x, np.float32)
+    return (x.view(np.uint32) >> 16).astype(np.uint16)

@@ -49,8 +49,10 @@ def zero_state(n, B, adam=True):
     return st
 
 
-def oracle_adam8(w, g, st, B, wd=0.0, t=1, flags=0, hp=ADAM, split=True):
-    """In place; splits the tensor at block boundaries over host threads (blocks are independent)."""
+def oracle_adam8(w, g, st, B, wd=0.0, t=1, flags=0, hp=ADAM, split=True, bf16=False):
+    """In place; splits the tensor at block boundaries over host threads (blocks are independent).
+    bf16: w and g are uint16 arrays of bfloat16 patterns."""
+    step = oracle.adam8bit_step_bf16 if bf16 else oracle.adam8bit_step
     qs, qu = codebooks()
     n = w.size
     nb = oracle.nblocks(n, B)
@@ -62,14 +64,15 @@ def oracle_adam8(w, g, st, B, wd=0.0, t=1, flags=0, hp=ADAM, split=True):
         if b0 >= b1:
             return
         s = slice(b0 * B, min(n, b1 * B))
-        oracle.adam8bit_step(w[s], g[s], st["m_q"][s], st["r_q"][s], st["N_m"][b0:b1], st["N_r"][b0:b1],
-                             qs, qu, B, hp["alpha"], hp["beta1"], hp["beta2"], hp["eps"], wd, t, flags)
+        step(w[s], g[s], st["m_q"][s], st["r_q"][s], st["N_m"][b0:b1], st["N_r"][b0:b1],
+             qs, qu, B, hp["alpha"], hp["beta1"], hp["beta2"], hp["eps"], wd, t, flags)
     list(pool().map(run, range(nthr)))
 
 
-def oracle_sgd8(w, g, st, B, wd=0.0, hp=SGD):
+def oracle_sgd8(w, g, st, B, wd=0.0, hp=SGD, bf16=False):
     qs, _ = codebooks()
-    oracle.sgd8bit_step(w, g, st["m_q"], st["N_m"], qs, B, hp["alpha"], hp["beta"], wd)
+    step = oracle.sgd8bit_step_bf16 if bf16 else oracle.sgd8bit_step
+    step(w, g, st["m_q"], st["N_m"], qs, B, hp["alpha"], hp["beta"], wd)
 
 
 def rel_err(w_gpu: np.ndarray, w_ref: np.ndarray) -> float:
