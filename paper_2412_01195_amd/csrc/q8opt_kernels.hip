@@ -968,7 +968,7 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
 }
 
 template <int B, typename WT>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -1017,7 +1017,7 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
 }
 
 template <int B, typename WT>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
@@ -1028,7 +1028,7 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void sg
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : Q8_MIN_WAVES)) void quantize_kernel(const void* qtab, const float* T,
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void quantize_kernel(const void* qtab, const float* T,
                                                                               uint8_t* TQ, float* N, int64_t n,
                                                                               int64_t nunits, Sched* sched)
 {
