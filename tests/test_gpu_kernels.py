@@ -320,3 +320,30 @@ def test_checkpoint_resume_and_fp32_state_import(q8, tabs):
     q8.dequantize_blockwise(tabs[0], mq, Nm, B, out)
     assert np.array_equal(out.cpu().numpy().view(np.uint32),
                           oracle.dequantize_blockwise(qs, st["m_q"], st["N_m"], B).view(np.uint32))
+
+
+@pytest.mark.parametrize("eps", [1e-8, 0.0, 2048.0], ids=["eps1e-8", "eps0", "eps2048"])
+def test_adam_gradient_scale_sweep_bitwise(q8, tabs, eps):
+    """Gradient magnitudes from the denormal range to 1e18, one decade per case, so that the rows
+    cross both ends of the range in which the weight update uses its short square root and
+    division (and eps = 2048 switches those off on the host): weights compared bit for bit."""
+    n, B = 256 * 5 + 77, 256
+    hp = dict(H.ADAM, eps=eps)
+    decades = range(-15, 19) if eps == 0.0 else range(-44, 19)
+    for k in decades:
+        rng = np.random.default_rng(1000 + k)
+        w_ref = synth.uniform_weights(500 + k, 0, n)
+        st = H.zero_state(n, B)
+        w = dev(w_ref); d = {key: dev(v) for key, v in st.items()}
+        for t in range(1, 4):
+            g = (rng.standard_normal(n) * 10.0 ** k).astype(np.float32)
+            if eps == 0.0:
+                g[g == 0] = np.float32(10.0 ** k)          # 0/0 is outside the method
+            if t == 2:
+                g[300:340] *= np.float32(1e-6)             # a few rows mix magnitudes
+            q8.adam8bit_step(w, dev(g), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **hp, t=t)
+            H.oracle_adam8(w_ref, g, st, B, t=t, hp=hp)
+            H.assert_state_equal("decade %d step %d" % (k, t), d, st, w, w_ref)
+            got = w.cpu().numpy()
+            same = (got.view(np.uint32) == w_ref.view(np.uint32)) | ((got == 0) & (w_ref == 0))
+            assert same.all(), "decade %d step %d: %d weights differ in their bits" % (k, t, int((~same).sum()))
