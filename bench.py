@@ -119,7 +119,7 @@ def build_workload(name, torch, q8opt, dev):
             t[0] += 1
             q8opt.adam8bit_step_bf16(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], tab_s, tab_u, B, **ADAM, t=t[0])
         # read w, g (2+2) and both codes (1+1), write w (2) and both codes (1+1), absmax as in the fp32 case
-        return wl["name"], n, 10 * n + 16 * (-(-n // B)), "adam8_kernel<%d, bf16>" % B, step, None, keep
+        return wl["name"], n, 10 * n + 16 * (-(-n // B)), "adam8_kernel<%d, Bf16>" % B, step, None, keep
     if name in ("1b", "1m", "sgd1b", "1b256", "100m"):
         wl = WORKLOADS[name]
         n, B = wl["n"], wl["B"]
@@ -132,10 +132,10 @@ def build_workload(name, torch, q8opt, dev):
             def step():
                 t[0] += 1
                 q8opt.adam8bit_step(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], tab_s, tab_u, B, **ADAM, t=t[0])
-            return wl["name"], n, algorithmic_bytes(n, B), "adam8_kernel<%d>" % B, step, (w, g, B), keep
+            return wl["name"], n, algorithmic_bytes(n, B), "adam8_kernel<%d, float>" % B, step, (w, g, B), keep
         def step():
             q8opt.sgd8bit_step(w, g, st["m_q"], st["N_m"], tab_s, B, 0.1, 0.9, 1e-4)
-        return wl["name"], n, 14 * n + 8 * (-(-n // B)), "sgd8_kernel<%d>" % B, step, None, keep
+        return wl["name"], n, 14 * n + 8 * (-(-n // B)), "sgd8_kernel<%d, float>" % B, step, None, keep
     if name in ("quant1b", "dequant1b"):
         n, B = 1_000_000_000, 2048
         nb = -(-n // B)
@@ -199,11 +199,11 @@ def build_workload(name, torch, q8opt, dev):
         def step():
             tt[0] += 1
             plan.multi_adam8bit_step(tab_s, tab_u, **ADAM, t=tt[0], **extra)
-        kern = "adam8_kernel<%d>" % B
+        kern = "adam8_kernel<%d, float>" % B
     else:
         def step():
             plan.multi_sgd8bit_step(tab_s, 0.1, 0.9, 1e-4)
-        kern = "sgd8_kernel<%d>" % B
+        kern = "sgd8_kernel<%d, float>" % B
     return desc, sum(sizes), alg, kern, step, None, keep
 
 
