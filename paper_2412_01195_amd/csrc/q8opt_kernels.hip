@@ -34,8 +34,11 @@
 // y = RN(1/N) is formed once and each element takes a faithful product and one
 // residual-correction fma pair (the classical Newton/Markstein division
 // sequence); blocks whose N lies outside [2^-60, 2^60] use the plain divide.  The
-// square root of the Adam denominator uses v_sqrt_f32 plus an exact neighbour test
-// on rows whose r are all at least 2^-100, the general sqrtf otherwise.
+// square root and the division of the Adam weight update take short, equally exact
+// forms on rows whose new states all lie in [2^-80, 2^40], sqrtf and a / b otherwise.
+//
+// Storage type: weights and gradients are binary32 or bfloat16 (template parameter
+// WT of the step kernels); the arithmetic and the 8-bit states are the same.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
@@ -847,22 +850,24 @@ struct Sched { unsigned long long next, done; };
 
 struct JobBox { long long job[2]; };
 
-// One draw hands a workgroup SPAN consecutive jobs.  With AHEAD the atomic of
-// the following draw is issued as soon as the current one has been read, which
-// hides its latency but lets every workgroup hold a claim one draw ahead (a wider
-// address window); the optimizer steps measured faster without it, the light
-// stand-alone quantizer faster with it.
-template <int SPAN, bool AHEAD>
+// One draw hands a workgroup SPAN consecutive jobs.  The first draw is issued at the
+// very start of the kernel, before the tables are staged, so that its latency hides
+// behind the staging.  With AHEAD the atomic of every following draw is issued as soon
+// as the current one has been read, which hides its latency too but lets every
+// workgroup hold a claim one draw ahead (a wider address window); the optimizer steps
+// measured faster without it, the light stand-alone quantizer faster with it.
+template <int SPAN>
 __device__ __forceinline__ void first_draw(Sched* sched, JobBox* box)
 {
-    if (AHEAD && threadIdx.x == 0)
+    if (threadIdx.x == 0)
         box->job[0] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
 }
 
+// `first` = this is the draw that first_draw has already issued (parity 0).
 template <int SPAN, bool AHEAD>
-__device__ __forceinline__ int64_t next_draw(Sched* sched, JobBox* box, int parity, int64_t njobs)
+__device__ __forceinline__ int64_t next_draw(Sched* sched, JobBox* box, int parity, int64_t njobs, bool first)
 {
-    if (!AHEAD && threadIdx.x == 0)
+    if (!AHEAD && !first && threadIdx.x == 0)
         box->job[parity] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
     __syncthreads();
     const long long j = box->job[parity];
@@ -872,6 +877,14 @@ __device__ __forceinline__ int64_t next_draw(Sched* sched, JobBox* box, int pari
     if (AHEAD && job < njobs && threadIdx.x == 0)
         box->job[parity ^ 1] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
     return job;
+}
+
+// A launch with no more draws' worth of jobs than workgroups gives every workgroup
+// exactly one draw: nobody needs to ask a second time.
+template <int SPAN>
+__device__ __forceinline__ bool single_draw(int64_t njobs)
+{
+    return njobs <= (int64_t)gridDim.x * SPAN;
 }
 
 __device__ __forceinline__ void leave(Sched* sched)
@@ -940,10 +953,11 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
     const int part = wave % S::WPB;
     const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
     SgdScalars none{};
-    first_draw<kStepSpan, false>(a.sched, &lds->box);
+    const bool once = single_draw<kStepSpan>(njobs);
     int xpar = 0;
-    for (int parity = 0;; parity ^= 1) {
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs);
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        if (once && !first) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs, first);
         if (j0 >= njobs) break;
         for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
@@ -971,6 +985,7 @@ template <int B, typename WT>
 __global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kStepSpan>(a.sched, &lds.box);
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     stage_second(lds.tab, a.qtab_u, threadIdx.x);
     __syncthreads();
@@ -989,10 +1004,11 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
     const int part = wave % S::WPB;
     const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
     AdamScalars none{};
-    first_draw<kStepSpan, false>(a.sched, &lds->box);
+    const bool once = single_draw<kStepSpan>(njobs);
     int xpar = 0;
-    for (int parity = 0;; parity ^= 1) {
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs);
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        if (once && !first) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs, first);
         if (j0 >= njobs) break;
         for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
@@ -1020,6 +1036,7 @@ template <int B, typename WT>
 __global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kStepSpan>(a.sched, &lds.box);
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     __syncthreads();
     if (sc.wd != 0.0f) sgd8_walk<B, WT, true>(a, sc, &lds);
@@ -1034,16 +1051,16 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2)
 {
     using S = Shape<B>;
     __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kQuantSpan>(sched, &lds.box);
     stage_first(lds.tab, qtab, threadIdx.x);
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int part = wave % S::WPB;
     const int64_t njobs = (nunits + S::UPJ - 1) / S::UPJ;
-    first_draw<kQuantSpan, true>(sched, &lds.box);
     int xpar = 0;
-    for (int parity = 0;; parity ^= 1) {
-        const int64_t j0 = next_draw<kQuantSpan, true>(sched, &lds.box, parity, njobs);
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        const int64_t j0 = next_draw<kQuantSpan, true>(sched, &lds.box, parity, njobs, first);
         if (j0 >= njobs) break;
         for (int k = 0; k < kQuantSpan && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
