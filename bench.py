@@ -280,8 +280,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 update, u8 states" + (", bf16 w and g" if args.workload == "bf16_1b" else ""), "data": "synthetic",
-        "config": {"workload": desc, "params": nparams, "hyper": ADAM if "adam" in kernel else None},
+        "dtype": "f32", "data": "synthetic",      # arithmetic type; storage: u8 states, f32 (or bf16) w and g
+        "config": {"workload": desc, "params": nparams, "hyper": ADAM if "adam" in kernel else None,
+                   "storage": "u8 states, %s w and g" % ("bf16" if args.workload == "bf16_1b" else "f32")},
         "hbm_gbps": achieved, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
