@@ -42,7 +42,9 @@
  *     stream, and up to 64 launches overlapping on different streams, are
  *     therefore independent.  A launch captured into a HIP graph keeps the
  *     counter it was given at capture time: replays of one graph are safe in
- *     sequence; do not replay it concurrently with itself.  The device entry
+ *     sequence; do not replay it concurrently with itself, and do not let a
+ *     replay overlap, on another stream, with other launches of this library
+ *     (one of them may be handed the same counter).  The device entry
  *     points enqueue exactly one kernel (no memset, no copy), so they can be
  *     captured once each kernel has been launched eagerly a first time (the
  *     first launch queries occupancy and the counter address, which is not
