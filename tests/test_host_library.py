@@ -125,3 +125,27 @@ def test_argument_validation_needs_no_gpu():
     assert L.q8_plan_create(t, 1, 3, C.byref(h)) == q8opt.EBLOCK
     assert L.q8_plan_destroy(None) == q8opt.EINVAL
     assert L.q8_multi_sgd8bit_step(None, a, 0.1, 0.9, 0.0, None) == q8opt.EINVAL
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as strict C99 and a C program must link
+    against the library's host entry points (no GPU is touched)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "c_abi.c"
+    src.write_text('#include <stdio.h>\n#include "q8opt.h"\n'
+                   "int main(void) {\n"
+                   "    float q[256];\n"
+                   "    if (q8_build_codebook(1, q) != Q8_OK) return 1;\n"
+                   "    if (sizeof(q8_tensor) != 72) return 2;\n"
+                   '    printf("%s %.9g %.9g\\n", q8_status_str(Q8_EBLOCK), (double)q[127], (double)q[255]);\n'
+                   "    return 0;\n}\n")
+    exe = tmp_path / "c_abi"
+    libdir = os.path.dirname(q8opt.LIB_PATH)
+    subprocess.check_call(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", os.path.join(root, "include"),
+                           "-o", str(exe), str(src), "-L", libdir, "-lq8opt", "-Wl,-rpath," + libdir])
+    out = subprocess.check_output([str(exe)], text=True).split()
+    assert float(out[-2]) == 0.0 and float(out[-1]) == 1.0
