@@ -35,12 +35,17 @@ def lib():
         L.oracle_sgd8bit_step.argtypes = [fp, fp, u8p, fp, fp, i64, i32, f32, f32, f32]
         L.oracle_adam8bit_step_bf16.argtypes = L.oracle_adam8bit_step.argtypes
         L.oracle_sgd8bit_step_bf16.argtypes = L.oracle_sgd8bit_step.argtypes
+        L.oracle_adam8bit_step_f16.argtypes = L.oracle_adam8bit_step.argtypes
+        L.oracle_sgd8bit_step_f16.argtypes = L.oracle_sgd8bit_step.argtypes
+        L.oracle_f16_to_f32.argtypes = [C.c_uint16]; L.oracle_f16_to_f32.restype = f32
+        L.oracle_f32_to_f16.argtypes = [f32]; L.oracle_f32_to_f16.restype = C.c_uint16
         L.oracle_bf16_to_f32.argtypes = [C.c_uint16]; L.oracle_bf16_to_f32.restype = f32
         L.oracle_f32_to_bf16.argtypes = [f32]; L.oracle_f32_to_bf16.restype = C.c_uint16
         for name in ("oracle_build_codebook", "oracle_nearest_code", "oracle_nearest_code_bruteforce",
                      "oracle_quantize_blockwise", "oracle_dequantize_blockwise", "oracle_adam32_step",
                      "oracle_sgd32_step", "oracle_adam8bit_step", "oracle_sgd8bit_step",
-                     "oracle_adam8bit_step_bf16", "oracle_sgd8bit_step_bf16"):
+                     "oracle_adam8bit_step_bf16", "oracle_sgd8bit_step_bf16",
+                     "oracle_adam8bit_step_f16", "oracle_sgd8bit_step_f16"):
             getattr(L, name).restype = i32
         _lib = L
     return _lib
@@ -132,6 +137,33 @@ def bf16_to_f32(h) -> float:
 
 def f32_to_bf16(x) -> int:
     return int(lib().oracle_f32_to_bf16(float(np.float32(x))))
+
+
+def f16_to_f32(h) -> float:
+    return float(lib().oracle_f16_to_f32(int(h)))
+
+
+def f32_to_f16(x) -> int:
+    return int(lib().oracle_f32_to_f16(float(np.float32(x))))
+
+
+def adam8bit_step_f16(w, g, m_q, r_q, N_m, N_r, q_signed, q_unsigned, B,
+                      alpha, beta1, beta2, eps, wd=0.0, t=1, flags=0):
+    """w, g: uint16 arrays holding IEEE binary16 patterns.  In place on w, m_q, r_q, N_m, N_r."""
+    n = w.size
+    assert g.size == n and m_q.size == n and r_q.size == n
+    assert N_m.size == nblocks(n, B) and N_r.size == nblocks(n, B)
+    _ok(lib().oracle_adam8bit_step_f16(_p(w, np.uint16), _p(g, np.uint16), _p(m_q, np.uint8), _p(r_q, np.uint8),
+                                       _p(N_m, np.float32), _p(N_r, np.float32),
+                                       _p(q_signed, np.float32), _p(q_unsigned, np.float32), n, B,
+                                       alpha, beta1, beta2, eps, wd, t, flags))
+
+
+def sgd8bit_step_f16(w, g, m_q, N_m, q_signed, B, alpha, beta, wd=0.0):
+    n = w.size
+    assert g.size == n and m_q.size == n and N_m.size == nblocks(n, B)
+    _ok(lib().oracle_sgd8bit_step_f16(_p(w, np.uint16), _p(g, np.uint16), _p(m_q, np.uint8), _p(N_m, np.float32),
+                                      _p(q_signed, np.float32), n, B, alpha, beta, wd))
 
 
 def adam8bit_step_bf16(w, g, m_q, r_q, N_m, N_r, q_signed, q_unsigned, B,

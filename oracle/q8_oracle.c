@@ -380,7 +380,68 @@ uint16_t oracle_f32_to_bf16(float f)
     return (uint16_t)hi;
 }
 
-int oracle_adam8bit_step_bf16(uint16_t *w, const uint16_t *g,
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) storage: same contract as    */
+/* bfloat16 above -- exact widening, one round-to-nearest-even of the new weight.    */
+float oracle_f16_to_f32(uint16_t h)
+{
+    int sign = (h >> 15) & 1, e = (h >> 10) & 0x1f, f = h & 0x3ff;
+    double v;
+    if (e == 0x1f)
+        v = f ? (double)NAN : (double)INFINITY;
+    else if (e == 0)
+        v = ldexp((double)f, -24);                     /* subnormal: f * 2^-24        */
+    else
+        v = ldexp((double)(1024 + f), e - 25);         /* (1 + f/1024) * 2^(e-15)     */
+    return (float)(sign ? -v : v);                     /* every binary16 is a binary32 */
+}
+
+/* Nearest binary16 to a finite binary32, ties to even: scale |x| so that one unit  */
+/* is the spacing of binary16 at that magnitude (2^-24 below 2^-14, else 2^(e-10)),  */
+/* round the scaled value to an integer with ties to even, and rebuild the pattern;  */
+/* a carry out of the fraction moves to the next exponent, past 65504 to infinity.   */
+uint16_t oracle_f32_to_f16(float x)
+{
+    uint16_t sign = signbit(x) ? 0x8000u : 0;
+    double a = fabs((double)x);
+    if (isnan(x))
+        return (uint16_t)(sign | 0x7e00u);
+    if (isinf(x))
+        return (uint16_t)(sign | 0x7c00u);
+    int e;                                             /* a = m * 2^e, m in [0.5, 1)   */
+    (void)frexp(a, &e);
+    int E = e - 1;                                     /* a in [2^E, 2^(E+1))          */
+    if (a == 0.0 || E < -14)
+        E = -14;                                       /* subnormal spacing 2^-24      */
+    double units = ldexp(a, 10 - E);                   /* exact: a power-of-two scale  */
+    double fl = floor(units), frac = units - fl;
+    long k = (long)fl;
+    if (frac > 0.5 || (frac == 0.5 && (k & 1)))
+        k += 1;
+    /* k in [0, 2048]: value = k * 2^(E-10) */
+    if (k == 2048) {                                   /* carried into the next binade */
+        k = 1024;
+        E += 1;
+    }
+    if (k < 1024)                                      /* subnormal (only when E = -14) */
+        return (uint16_t)(sign | (uint16_t)k);
+    if (E > 15)
+        return (uint16_t)(sign | 0x7c00u);
+    return (uint16_t)(sign | (uint16_t)((E + 15) << 10) | (uint16_t)(k - 1024));
+}
+
+enum { STORE_BF16 = 0, STORE_F16 = 1 };
+
+static float widen(uint16_t h, int kind)
+{
+    return kind == STORE_F16 ? oracle_f16_to_f32(h) : oracle_bf16_to_f32(h);
+}
+
+static uint16_t narrow(float x, int kind)
+{
+    return kind == STORE_F16 ? oracle_f32_to_f16(x) : oracle_f32_to_bf16(x);
+}
+
+static int adam8bit_step_lowp(uint16_t *w, const uint16_t *g, int kind,
                               uint8_t *m_q, uint8_t *r_q, float *N_m, float *N_r,
                               const float *q_signed, const float *q_unsigned,
                               int64_t n, int B,
@@ -396,9 +457,9 @@ int oracle_adam8bit_step_bf16(uint16_t *w, const uint16_t *g,
         for (int64_t i = 0; i < len; ++i) {
             float m_prev = q_signed[m_q[st + i]] * N_m[b];
             float r_prev = q_unsigned[r_q[st + i]] * N_r[b];
-            float w32 = oracle_bf16_to_f32(w[st + i]);
-            adam_element(&s, &w32, oracle_bf16_to_f32(g[st + i]), m_prev, r_prev, &mbuf[i], &rbuf[i]);
-            w[st + i] = oracle_f32_to_bf16(w32);
+            float w32 = widen(w[st + i], kind);
+            adam_element(&s, &w32, widen(g[st + i], kind), m_prev, r_prev, &mbuf[i], &rbuf[i]);
+            w[st + i] = narrow(w32, kind);
         }
         quantize_block(q_signed, mbuf, len, m_q + st, N_m + b);
         quantize_block(q_unsigned, rbuf, len, r_q + st, N_r + b);
@@ -406,7 +467,7 @@ int oracle_adam8bit_step_bf16(uint16_t *w, const uint16_t *g,
     return 0;
 }
 
-int oracle_sgd8bit_step_bf16(uint16_t *w, const uint16_t *g, uint8_t *m_q, float *N_m,
+static int sgd8bit_step_lowp(uint16_t *w, const uint16_t *g, int kind, uint8_t *m_q, float *N_m,
                              const float *q_signed, int64_t n, int B,
                              float alpha, float beta, float wd)
 {
@@ -417,11 +478,41 @@ int oracle_sgd8bit_step_bf16(uint16_t *w, const uint16_t *g, uint8_t *m_q, float
         int64_t len = (n - st < B) ? n - st : B;
         for (int64_t i = 0; i < len; ++i) {
             float m_prev = q_signed[m_q[st + i]] * N_m[b];
-            float w32 = oracle_bf16_to_f32(w[st + i]);
-            sgd_element(alpha, beta, wd, &w32, oracle_bf16_to_f32(g[st + i]), m_prev, &mbuf[i]);
-            w[st + i] = oracle_f32_to_bf16(w32);
+            float w32 = widen(w[st + i], kind);
+            sgd_element(alpha, beta, wd, &w32, widen(g[st + i], kind), m_prev, &mbuf[i]);
+            w[st + i] = narrow(w32, kind);
         }
         quantize_block(q_signed, mbuf, len, m_q + st, N_m + b);
     }
     return 0;
+}
+
+int oracle_adam8bit_step_bf16(uint16_t *w, const uint16_t *g,
+                              uint8_t *m_q, uint8_t *r_q, float *N_m, float *N_r,
+                              const float *q_signed, const float *q_unsigned, int64_t n, int B,
+                              float alpha, float beta1, float beta2, float eps, float wd, int64_t t, int flags)
+{
+    return adam8bit_step_lowp(w, g, STORE_BF16, m_q, r_q, N_m, N_r, q_signed, q_unsigned, n, B,
+                              alpha, beta1, beta2, eps, wd, t, flags);
+}
+
+int oracle_adam8bit_step_f16(uint16_t *w, const uint16_t *g,
+                             uint8_t *m_q, uint8_t *r_q, float *N_m, float *N_r,
+                             const float *q_signed, const float *q_unsigned, int64_t n, int B,
+                             float alpha, float beta1, float beta2, float eps, float wd, int64_t t, int flags)
+{
+    return adam8bit_step_lowp(w, g, STORE_F16, m_q, r_q, N_m, N_r, q_signed, q_unsigned, n, B,
+                              alpha, beta1, beta2, eps, wd, t, flags);
+}
+
+int oracle_sgd8bit_step_bf16(uint16_t *w, const uint16_t *g, uint8_t *m_q, float *N_m,
+                             const float *q_signed, int64_t n, int B, float alpha, float beta, float wd)
+{
+    return sgd8bit_step_lowp(w, g, STORE_BF16, m_q, N_m, q_signed, n, B, alpha, beta, wd);
+}
+
+int oracle_sgd8bit_step_f16(uint16_t *w, const uint16_t *g, uint8_t *m_q, float *N_m,
+                            const float *q_signed, int64_t n, int B, float alpha, float beta, float wd)
+{
+    return sgd8bit_step_lowp(w, g, STORE_F16, m_q, N_m, q_signed, n, B, alpha, beta, wd);
 }
