@@ -34,6 +34,7 @@ WORKLOADS = {
     "1b256": dict(n=1_000_000_000, B=256, name="flat fp32 tensor, 1e9 params, 8-bit Adam, B=256, grads N(0,1e-3)"),
     "100m": dict(n=100_000_000, B=2048, name="flat fp32 tensor, 1e8 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "bf16_1b": dict(n=1_000_000_000, B=2048, name="flat bfloat16 weights and gradients (extension), 1e9 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
+    "f16_1b": dict(n=1_000_000_000, B=2048, name="flat binary16 weights and gradients (extension), 1e9 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "sgd1b": dict(n=1_000_000_000, B=2048, name="flat fp32 tensor, 1e9 params, 8-bit SGD momentum, B=2048, grads N(0,1e-3)"),
 }
 
@@ -107,19 +108,21 @@ def build_workload(name, torch, q8opt, dev):
             st.update(r_q=torch.zeros(n, dtype=torch.uint8, device=dev), N_r=torch.zeros(nb, device=dev))
         return st
 
-    if name == "bf16_1b":
+    if name in ("bf16_1b", "f16_1b"):
         wl = WORKLOADS[name]
         n, B = wl["n"], wl["B"]
-        w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen).to(torch.bfloat16)
-        g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen).to(torch.bfloat16)
+        dt, fn, tag = ((torch.bfloat16, q8opt.adam8bit_step_bf16, "Bf16") if name == "bf16_1b"
+                       else (torch.float16, q8opt.adam8bit_step_f16, "F16"))
+        w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen).to(dt)
+        g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen).to(dt)
         st = state8(n, B, True)
         t = [0]
 
         def step():
             t[0] += 1
-            q8opt.adam8bit_step_bf16(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], tab_s, tab_u, B, **ADAM, t=t[0])
+            fn(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], tab_s, tab_u, B, **ADAM, t=t[0])
         # read w, g (2+2) and both codes (1+1), write w (2) and both codes (1+1), absmax as in the fp32 case
-        return wl["name"], n, 10 * n + 16 * (-(-n // B)), "adam8_kernel<%d, Bf16>" % B, step, None, keep
+        return wl["name"], n, 10 * n + 16 * (-(-n // B)), "adam8_kernel<%d, %s>" % (B, tag), step, None, keep
     if name in ("1b", "1m", "sgd1b", "1b256", "100m"):
         wl = WORKLOADS[name]
         n, B = wl["n"], wl["B"]
@@ -213,7 +216,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="1b",
-                    choices=["1b", "1m", "1b256", "100m", "bf16_1b", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5", "df"],
+                    choices=["1b", "1m", "1b256", "100m", "bf16_1b", "f16_1b", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5", "df"],
                     help="1b (default) = configuration 4, the one the headline metric is quoted on")
     ap.add_argument("--block-size", type=int, default=0,
                     help="override the block size B of a flat workload (block-size sweep; not the headline line)")
@@ -282,7 +285,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",      # arithmetic type; storage: u8 states, f32 (or bf16) w and g
         "config": {"workload": desc, "params": nparams, "hyper": ADAM if "adam" in kernel else None,
-                   "storage": "u8 states, %s w and g" % ("bf16" if args.workload == "bf16_1b" else "f32")},
+                   "storage": "u8 states, %s w and g" % {"bf16_1b": "bf16", "f16_1b": "f16"}.get(args.workload, "f32")},
         "hbm_gbps": achieved, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

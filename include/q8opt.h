@@ -25,8 +25,8 @@
  *   - B is a power of two in [64, 4096].  A tensor of n elements has
  *     ceil(n / B) blocks; the last block may be short (it is quantized over
  *     its valid elements only).  n == 0 is a no-op.
- *   - fp32 tensors (w, g, T, TD) must be 16-byte aligned, bfloat16 w and g
- *     (the _bf16 entry points) 8-byte aligned, code arrays and absmax arrays
+ *   - fp32 tensors (w, g, T, TD) must be 16-byte aligned, 16-bit w and g
+ *     (the _bf16 and _f16 entry points) 8-byte aligned, code arrays and absmax arrays
  *     4-byte aligned, qtables 16-byte aligned (else Q8_EALIGN).
  *   - Inputs must be finite; results for NaN/Inf inputs are unspecified (no
  *     out-of-bounds access happens).
@@ -157,13 +157,14 @@ Q8_API q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, float* 
                           float alpha, float beta, float weight_decay, void* stream);
 
 /*
- * Weights and gradients stored as bfloat16 (an extension; the paper keeps both
- * in binary32).  bfloat16 = the upper 16 bits of a binary32, passed as uint16_t.
+ * Weights and gradients stored in 16 bits (an extension; the paper keeps both in
+ * binary32): bfloat16 (the upper 16 bits of a binary32; _bf16) or IEEE binary16
+ * (_f16, subnormals kept, overflow rounds to infinity), passed as uint16_t.
  * Each stored w and g is widened exactly, the step runs in binary32 exactly as
  * in the entry points above (same formulas, same 8-bit states and block maxima),
- * and the new weight is rounded once, to nearest-even, back to bfloat16.  An
- * update smaller than half a bfloat16 unit in the last place of its weight
- * therefore leaves that weight unchanged; the states still advance.
+ * and the new weight is rounded once, to nearest-even, back to the storage
+ * type.  An update smaller than half a unit in the last place of its stored
+ * weight therefore leaves that weight unchanged; the states still advance.
  * Arguments as above except for the element type of w (in place) and g.
  */
 Q8_API q8_status q8_adam8bit_step_bf16(uint16_t* w, const uint16_t* g,
@@ -175,6 +176,15 @@ Q8_API q8_status q8_adam8bit_step_bf16(uint16_t* w, const uint16_t* g,
 Q8_API q8_status q8_sgd8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8_t* m_q, float* N_m,
                                const void* qtable_signed, int64_t n, int B,
                                float alpha, float beta, float weight_decay, void* stream);
+Q8_API q8_status q8_adam8bit_step_f16(uint16_t* w, const uint16_t* g,
+                               uint8_t* m_q, uint8_t* r_q, float* N_m, float* N_r,
+                               const void* qtable_signed, const void* qtable_unsigned,
+                               int64_t n, int B,
+                               float alpha, float beta1, float beta2, float eps,
+                               float weight_decay, int64_t t, int flags, void* stream);
+Q8_API q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t* m_q, float* N_m,
+                              const void* qtable_signed, int64_t n, int B,
+                              float alpha, float beta, float weight_decay, void* stream);
 
 /*
  * Multi-tensor launch: one kernel launch updates a whole list of parameter
@@ -186,8 +196,9 @@ Q8_API q8_status q8_sgd8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8_t* m
  * (synchronous); the tensors themselves stay owned by the caller and must
  * outlive the plan's use.  r_q/N_r/r_f32 may be NULL for a plan that is only
  * used with the SGD entry point.  w and g of every tensor of a plan hold
- * binary32 (q8_plan_create) or bfloat16 (q8_plan_create_bf16, semantics of the
- * _bf16 steps above; the 32-bit states m_f32/r_f32 stay binary32).
+ * binary32 (q8_plan_create), bfloat16 (q8_plan_create_bf16) or binary16
+ * (q8_plan_create_f16), with the semantics of the 16-bit steps above; the
+ * 32-bit states m_f32/r_f32 stay binary32.
  */
 typedef struct q8_tensor {
     void*        w;
@@ -205,6 +216,7 @@ typedef struct q8_plan q8_plan;
 
 Q8_API q8_status q8_plan_create(const q8_tensor* list /* host */, int count, int B, q8_plan** out);
 Q8_API q8_status q8_plan_create_bf16(const q8_tensor* list /* host */, int count, int B, q8_plan** out);
+Q8_API q8_status q8_plan_create_f16(const q8_tensor* list /* host */, int count, int B, q8_plan** out);
 Q8_API q8_status q8_plan_destroy(q8_plan* plan);
 
 Q8_API q8_status q8_multi_adam8bit_step(q8_plan* plan,

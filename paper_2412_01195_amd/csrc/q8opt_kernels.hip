@@ -37,8 +37,8 @@
 // square root and the division of the Adam weight update take short, equally exact
 // forms on rows whose new states all lie in [2^-80, 2^40], sqrtf and a / b otherwise.
 //
-// Storage type: weights and gradients are binary32 or bfloat16 (template parameter
-// WT of the step kernels); the arithmetic and the 8-bit states are the same.
+// Storage type: weights and gradients are binary32, bfloat16 or binary16 (template
+// parameter WT of the step kernels); the arithmetic and the 8-bit states are the same.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
@@ -83,6 +83,7 @@ typedef Q8_GLOBAL const uint16_t gcu16;
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 typedef Q8_GLOBAL v2u gv2u;
 typedef Q8_GLOBAL const v2u gcv2u;
 
@@ -378,39 +379,71 @@ __device__ __forceinline__ void store4b(gbyte* p, int cnt, uint32_t v)
     }
 }
 
-// Storage type WT of weights and gradients: float, or Bf16 (bfloat16 = the upper
-// half of a binary32).  Widening is exact; narrowing is the hardware's
-// round-to-nearest-even conversion (v_cvt_pk_bf16_f32), applied once to the new weight.
+// Storage type WT of weights and gradients: float, Bf16 (bfloat16 = the upper half of
+// a binary32) or F16 (IEEE binary16).  Widening is exact; narrowing is the hardware's
+// round-to-nearest-even conversion (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32, binary16
+// subnormals kept), applied once to the new weight.
 struct Bf16 { uint16_t bits; };
+struct F16 { uint16_t bits; };
 
 template <typename WT> struct Wide;
 template <> struct Wide<float> { typedef gfloat* ptr; typedef gcfloat* cptr; };
 template <> struct Wide<Bf16> { typedef gu16* ptr; typedef gcu16* cptr; };
+template <> struct Wide<F16> { typedef gu16* ptr; typedef gcu16* cptr; };
 
-__device__ __forceinline__ void load4w(gcfloat* p, int cnt, float (&v)[4]) { load4f(p, cnt, v); }
-__device__ __forceinline__ void store4w(gfloat* p, int cnt, const float (&v)[4]) { store4f(p, cnt, v); }
-
-__device__ __forceinline__ void load4w(gcu16* p, int cnt, float (&v)[4])
+template <typename WT> __device__ __forceinline__ void widen2(uint32_t pair, float& lo, float& hi);
+template <> __device__ __forceinline__ void widen2<Bf16>(uint32_t pair, float& lo, float& hi)
 {
-    if (cnt == 4) {
-        const v2u t = __builtin_nontemporal_load((gcv2u*)p);
-        v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
-        v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = (j < cnt) ? __uint_as_float((uint32_t)p[j] << 16) : 0.0f;
-    }
+    lo = __uint_as_float(pair << 16);
+    hi = __uint_as_float(pair & 0xffff0000u);
+}
+template <> __device__ __forceinline__ void widen2<F16>(uint32_t pair, float& lo, float& hi)
+{
+    const v2f f = __builtin_convertvector(__builtin_bit_cast(v2h, pair), v2f);
+    lo = f.x;
+    hi = f.y;
 }
 
-__device__ __forceinline__ uint32_t narrow2(float lo, float hi)
+template <typename WT> __device__ __forceinline__ uint32_t narrow2(float lo, float hi);
+template <> __device__ __forceinline__ uint32_t narrow2<Bf16>(float lo, float hi)
 {
     const v2f x = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, v2bf));
 }
+template <> __device__ __forceinline__ uint32_t narrow2<F16>(float lo, float hi)
+{
+    const v2f x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, v2h));
+}
 
+template <typename WT>
+__device__ __forceinline__ void load4w(gcfloat* p, int cnt, float (&v)[4]) { load4f(p, cnt, v); }
+template <typename WT>
+__device__ __forceinline__ void store4w(gfloat* p, int cnt, const float (&v)[4]) { store4f(p, cnt, v); }
+
+template <typename WT>
+__device__ __forceinline__ void load4w(gcu16* p, int cnt, float (&v)[4])
+{
+    uint32_t a, b;
+    if (cnt == 4) {
+        const v2u t = __builtin_nontemporal_load((gcv2u*)p);
+        a = t.x;
+        b = t.y;
+    } else {
+        uint32_t h[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) h[j] = (j < cnt) ? (uint32_t)p[j] : 0u;
+        a = h[0] | (h[1] << 16);
+        b = h[2] | (h[3] << 16);
+    }
+    widen2<WT>(a, v[0], v[1]);
+    widen2<WT>(b, v[2], v[3]);
+}
+
+template <typename WT>
 __device__ __forceinline__ void store4w(gu16* p, int cnt, const float (&v)[4])
 {
-    const uint32_t a = narrow2(v[0], v[1]), b = narrow2(v[2], v[3]);
+    const uint32_t a = narrow2<WT>(v[0], v[1]), b = narrow2<WT>(v[2], v[3]);
     if (cnt == 4) {
         const v2u t = {a, b};
         __builtin_nontemporal_store(t, (gv2u*)p);
@@ -660,8 +693,8 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4w(w + e0, cnt, wv[r]);
-            load4w(g + e0, cnt, gv[r]);
+            load4w<WT>(w + e0, cnt, wv[r]);
+            load4w<WT>(g + e0, cnt, gv[r]);
             mq[r] = load4b(m_q + e0, cnt);
             rq[r] = load4b(r_q + e0, cnt);
         } else {
@@ -708,7 +741,7 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
 #pragma unroll
             for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, false>(sc, wv[r][j], mnew[j], rnew[j]);
         }
-        if (FULL || cnt > 0) store4w(w + e0, cnt, wv[r]);
+        if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             gv[r][j] = mnew[j];
@@ -739,8 +772,8 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4w(w + e0, cnt, wv[r]);
-            load4w(g + e0, cnt, gv[r]);
+            load4w<WT>(w + e0, cnt, wv[r]);
+            load4w<WT>(g + e0, cnt, gv[r]);
             mq[r] = load4b(m_q + e0, cnt);
         } else {
 #pragma unroll
@@ -765,7 +798,7 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
             gv[r][j] = m_new;
         }
         amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], gv[r]);
-        if (FULL || cnt > 0) store4w(w + e0, cnt, wv[r]);
+        if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
     }
     reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
     BlockNorm bn[1][S::NBLK];
@@ -789,8 +822,8 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, cons
         const int cnt = lane_count(n, e0);
         if (cnt == 0) continue;
         float wv[4], gv[4], mv[4], rv[4] = {0.f, 0.f, 0.f, 0.f};
-        load4w(w + e0, cnt, wv);
-        load4w(g + e0, cnt, gv);
+        load4w<WT>(w + e0, cnt, wv);
+        load4w<WT>(g + e0, cnt, gv);
         load4f(m + e0, cnt, mv);
         if (ADAM) load4f(rr + e0, cnt, rv);
 #pragma unroll
@@ -804,7 +837,7 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, cons
                 else sgd_element<false>(ss, wv[j], gv[j], mv[j], mv[j]);
             }
         }
-        store4w(w + e0, cnt, wv);
+        store4w<WT>(w + e0, cnt, wv);
         store4f(m + e0, cnt, mv);
         if (ADAM) store4f(rr + e0, cnt, rv);
     }
@@ -1279,6 +1312,8 @@ q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* 
 
 }  // namespace
 
+enum { kStoreF32 = 0, kStoreBf16 = 1, kStoreF16 = 2 };
+
 struct q8_plan {
     TensorDesc* d_descs;
     TileRef* d_tiles;
@@ -1286,7 +1321,7 @@ struct q8_plan {
     int count;
     int B;
     bool has_r;        // every tensor carries second-state storage (usable with Adam)
-    bool bf16;         // w and g of every tensor hold bfloat16
+    int store;         // element type of every w and g: kStoreF32, kStoreBf16, kStoreF16
 };
 
 extern "C" q8_status q8_quantize_blockwise(const void* qtable, const float* T, int64_t n, int B,
@@ -1386,6 +1421,15 @@ extern "C" q8_status q8_adam8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8
                            weight_decay, t, flags, stream);
 }
 
+extern "C" q8_status q8_adam8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t* m_q, uint8_t* r_q, float* N_m,
+                                          float* N_r, const void* qtable_signed, const void* qtable_unsigned,
+                                          int64_t n, int B, float alpha, float beta1, float beta2, float eps,
+                                          float weight_decay, int64_t t, int flags, void* stream)
+{
+    return adam_step<F16>(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, n, B, alpha, beta1, beta2, eps,
+                          weight_decay, t, flags, stream);
+}
+
 extern "C" q8_status q8_sgd8bit_step(float* w, const float* g, uint8_t* m_q, float* N_m, const void* qtable_signed,
                                      int64_t n, int B, float alpha, float beta, float weight_decay, void* stream)
 {
@@ -1399,16 +1443,23 @@ extern "C" q8_status q8_sgd8bit_step_bf16(uint16_t* w, const uint16_t* g, uint8_
     return sgd_step<Bf16>(w, g, m_q, N_m, qtable_signed, n, B, alpha, beta, weight_decay, stream);
 }
 
+extern "C" q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t* m_q, float* N_m,
+                                         const void* qtable_signed, int64_t n, int B, float alpha, float beta,
+                                         float weight_decay, void* stream)
+{
+    return sgd_step<F16>(w, g, m_q, N_m, qtable_signed, n, B, alpha, beta, weight_decay, stream);
+}
+
 namespace {
 
-q8_status plan_create(const q8_tensor* list, int count, int B, bool bf16, q8_plan** out)
+q8_status plan_create(const q8_tensor* list, int count, int B, int store, q8_plan** out)
 {
     if (!out) return Q8_EINVAL;
     *out = nullptr;
     if (!list || count <= 0) return Q8_EINVAL;
     if (!valid_block(B)) return Q8_EBLOCK;
     const int64_t te = unit_elems(B);
-    const size_t wg_al = bf16 ? wg_align<Bf16>() : wg_align<float>();
+    const size_t wg_al = (store == kStoreF32) ? wg_align<float>() : wg_align<Bf16>();
     int64_t ntiles = 0;
     bool has_r = true;
     for (int i = 0; i < count; ++i) {
@@ -1459,7 +1510,7 @@ q8_status plan_create(const q8_tensor* list, int count, int B, bool bf16, q8_pla
     p->count = count;
     p->B = B;
     p->has_r = has_r;
-    p->bf16 = bf16;
+    p->store = store;
     *out = p;
     return Q8_OK;
 }
@@ -1468,12 +1519,17 @@ q8_status plan_create(const q8_tensor* list, int count, int B, bool bf16, q8_pla
 
 extern "C" q8_status q8_plan_create(const q8_tensor* list, int count, int B, q8_plan** out)
 {
-    return plan_create(list, count, B, false, out);
+    return plan_create(list, count, B, kStoreF32, out);
 }
 
 extern "C" q8_status q8_plan_create_bf16(const q8_tensor* list, int count, int B, q8_plan** out)
 {
-    return plan_create(list, count, B, true, out);
+    return plan_create(list, count, B, kStoreBf16, out);
+}
+
+extern "C" q8_status q8_plan_create_f16(const q8_tensor* list, int count, int B, q8_plan** out)
+{
+    return plan_create(list, count, B, kStoreF16, out);
 }
 
 extern "C" q8_status q8_plan_destroy(q8_plan* plan)
@@ -1502,8 +1558,11 @@ extern "C" q8_status q8_multi_adam8bit_step(q8_plan* plan, const void* qtable_si
     a.nunits = plan->ntiles;
     a.qtab_s = qtable_signed;
     a.qtab_u = qtable_unsigned;
-    if (plan->bf16) {
+    if (plan->store == kStoreBf16) {
         Q8_DISPATCH_B(plan->B, return (launch_adam<kB, Bf16>(a, sc, static_cast<hipStream_t>(stream))));
+    }
+    if (plan->store == kStoreF16) {
+        Q8_DISPATCH_B(plan->B, return (launch_adam<kB, F16>(a, sc, static_cast<hipStream_t>(stream))));
     }
     Q8_DISPATCH_B(plan->B, return (launch_adam<kB, float>(a, sc, static_cast<hipStream_t>(stream))));
     return Q8_OK;
@@ -1521,8 +1580,11 @@ extern "C" q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_sig
     a.nunits = plan->ntiles;
     a.qtab_s = qtable_signed;
     SgdScalars sc{alpha, beta, weight_decay};
-    if (plan->bf16) {
+    if (plan->store == kStoreBf16) {
         Q8_DISPATCH_B(plan->B, return (launch_sgd<kB, Bf16>(a, sc, static_cast<hipStream_t>(stream))));
+    }
+    if (plan->store == kStoreF16) {
+        Q8_DISPATCH_B(plan->B, return (launch_sgd<kB, F16>(a, sc, static_cast<hipStream_t>(stream))));
     }
     Q8_DISPATCH_B(plan->B, return (launch_sgd<kB, float>(a, sc, static_cast<hipStream_t>(stream))));
     return Q8_OK;

@@ -8,7 +8,7 @@ arithmetic step runs in libq8opt.so through one multi-tensor launch per paramete
     opt = Adam8bit(..., weight_decay=0.05, decoupled_weight_decay=True, bias_correction=True)   # AdamW
     opt = SGD8bit(model.parameters(), lr=0.1, momentum=0.9, weight_decay=1e-4)
 
-Parameters must be contiguous CUDA tensors, all float32 or all bfloat16 within a group
+Parameters must be contiguous CUDA tensors, all float32, all bfloat16 or all float16 within a group
 (gradients in the same dtype).  Tensors with fewer than `min_8bit_size` elements keep
 32-bit states (same formulas, no quantization).  Optimizer state lives in ordinary torch
 tensors, so `state_dict()` / `load_state_dict()` checkpoint and resume it.
@@ -85,8 +85,8 @@ class _Q8Optimizer(torch.optim.Optimizer):
                 raise RuntimeError("sparse gradients are not supported")
             if not p.is_cuda or not p.is_contiguous() or not g.is_contiguous():
                 raise RuntimeError("parameters and gradients must be contiguous CUDA tensors")
-            if p.dtype not in (torch.float32, torch.bfloat16) or g.dtype != p.dtype:
-                raise RuntimeError("parameters and gradients must both be float32 or both bfloat16")
+            if p.dtype not in (torch.float32, torch.bfloat16, torch.float16) or g.dtype != p.dtype:
+                raise RuntimeError("parameters and gradients must share one of float32, bfloat16, float16")
             if dtype is None:
                 dtype, device = p.dtype, p.device
             elif p.dtype != dtype or p.device != device:
@@ -106,7 +106,7 @@ class _Q8Optimizer(torch.optim.Optimizer):
                 torch.cuda.current_stream(device).synchronize()     # work using the old table may be in flight
                 cached[1].destroy()
             with torch.cuda.device(device):
-                plan = q8opt.Plan(entries, group["block_size"], bf16=(dtype == torch.bfloat16))
+                plan = q8opt.Plan(entries, group["block_size"], wg_dtype=str(dtype).replace("torch.", ""))
             self._plans[gi] = cached = (sig, plan, device)
         return cached[1], cached[2]
 

@@ -26,6 +26,7 @@ EXPORTS = (
     "q8_quantize_blockwise", "q8_dequantize_blockwise", "q8_adam8bit_step", "q8_sgd8bit_step",
     "q8_plan_create", "q8_plan_destroy", "q8_multi_adam8bit_step", "q8_multi_sgd8bit_step",
     "q8_adam8bit_step_bf16", "q8_sgd8bit_step_bf16", "q8_plan_create_bf16",
+    "q8_adam8bit_step_f16", "q8_sgd8bit_step_f16", "q8_plan_create_f16",
 )
 
 
@@ -63,8 +64,11 @@ def lib():
         L.q8_sgd8bit_step.argtypes = [vp, vp, vp, vp, vp, i64, i32, f32, f32, f32, vp]
         L.q8_adam8bit_step_bf16.argtypes = L.q8_adam8bit_step.argtypes
         L.q8_sgd8bit_step_bf16.argtypes = L.q8_sgd8bit_step.argtypes
+        L.q8_adam8bit_step_f16.argtypes = L.q8_adam8bit_step.argtypes
+        L.q8_sgd8bit_step_f16.argtypes = L.q8_sgd8bit_step.argtypes
         L.q8_plan_create.argtypes = [C.POINTER(q8_tensor), i32, i32, C.POINTER(vp)]
         L.q8_plan_create_bf16.argtypes = L.q8_plan_create.argtypes
+        L.q8_plan_create_f16.argtypes = L.q8_plan_create.argtypes
         L.q8_plan_destroy.argtypes = [vp]
         L.q8_multi_adam8bit_step.argtypes = [vp, vp, vp, f32, f32, f32, f32, f32, i64, i32, vp]
         L.q8_multi_sgd8bit_step.argtypes = [vp, vp, f32, f32, f32, vp]
@@ -178,6 +182,13 @@ def adam8bit_step_bf16(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned,
           alpha, beta1, beta2, eps, weight_decay, t, flags, n)
 
 
+def adam8bit_step_f16(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, B: int,
+                      alpha, beta1, beta2, eps, weight_decay=0.0, t=1, flags=0, n: Optional[int] = None):
+    """w, g: torch.float16 tensors."""
+    _adam("q8_adam8bit_step_f16", "float16", w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, B,
+          alpha, beta1, beta2, eps, weight_decay, t, flags, n)
+
+
 def sgd8bit_step(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight_decay=0.0, n: Optional[int] = None):
     _sgd("q8_sgd8bit_step", "float32", w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n)
 
@@ -188,23 +199,33 @@ def sgd8bit_step_bf16(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight
     _sgd("q8_sgd8bit_step_bf16", "bfloat16", w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n)
 
 
+def sgd8bit_step_f16(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight_decay=0.0,
+                     n: Optional[int] = None):
+    """w, g: torch.float16 tensors."""
+    _sgd("q8_sgd8bit_step_f16", "float16", w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n)
+
+
 class Plan:
     """q8_plan: a list of parameter tensors updated by one launch.
 
     Each entry is a dict with keys w, g and either (m_q, N_m[, r_q, N_r]) or (m_f32[, r_f32]).
-    bf16=True: every w and g is a torch.bfloat16 tensor (q8_plan_create_bf16)."""
+    wg_dtype: "float32" (default), "bfloat16" or "float16" = element type of every w and g
+    (q8_plan_create, q8_plan_create_bf16, q8_plan_create_f16); bf16=True is short for "bfloat16"."""
 
-    def __init__(self, tensors: Sequence[dict], B: int, bf16: bool = False):
+    def __init__(self, tensors: Sequence[dict], B: int, bf16: bool = False, wg_dtype: Optional[str] = None):
         arr = (q8_tensor * len(tensors))()
         self._keep = list(tensors)
-        wg = "bfloat16" if bf16 else "float32"
+        wg = wg_dtype or ("bfloat16" if bf16 else "float32")
+        if wg not in ("float32", "bfloat16", "float16"):
+            raise ValueError("wg_dtype must be float32, bfloat16 or float16")
         for i, t in enumerate(tensors):
             arr[i].w = _ptr(t["w"], wg); arr[i].g = _ptr(t["g"], wg); arr[i].n = t["w"].numel()
             arr[i].m_q = _ptr(t.get("m_q"), "uint8"); arr[i].r_q = _ptr(t.get("r_q"), "uint8")
             arr[i].N_m = _ptr(t.get("N_m"), "float32"); arr[i].N_r = _ptr(t.get("N_r"), "float32")
             arr[i].m_f32 = _ptr(t.get("m_f32"), "float32"); arr[i].r_f32 = _ptr(t.get("r_f32"), "float32")
         h = C.c_void_p()
-        create = lib().q8_plan_create_bf16 if bf16 else lib().q8_plan_create
+        create = {"float32": lib().q8_plan_create, "bfloat16": lib().q8_plan_create_bf16,
+                  "float16": lib().q8_plan_create_f16}[wg]
         _check(create(arr, len(tensors), B, C.byref(h)), "q8_plan_create")
         self._h = h
 

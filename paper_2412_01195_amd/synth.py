@@ -160,3 +160,9 @@ def bf16_bits(x: np.ndarray) -> np.ndarray:
     (plain truncation -- this only manufactures representable test inputs)."""
     x = np.ascontiguousarray(x, np.float32)
     return (x.view(np.uint32) >> 16).astype(np.uint16)
+
+
+def f16_bits(x: np.ndarray) -> np.ndarray:
+    """Inputs for the binary16-storage entry points: numpy's float16 cast of each value, as bit
+    patterns (this only manufactures representable test inputs)."""
+    return np.ascontiguousarray(x, np.float32).astype(np.float16).view(np.uint16)

@@ -49,10 +49,10 @@ def zero_state(n, B, adam=True):
     return st
 
 
-def oracle_adam8(w, g, st, B, wd=0.0, t=1, flags=0, hp=ADAM, split=True, bf16=False):
+def oracle_adam8(w, g, st, B, wd=0.0, t=1, flags=0, hp=ADAM, split=True, bf16=False, f16=False):
     """In place; splits the tensor at block boundaries over host threads (blocks are independent).
-    bf16: w and g are uint16 arrays of bfloat16 patterns."""
-    step = oracle.adam8bit_step_bf16 if bf16 else oracle.adam8bit_step
+    bf16 / f16: w and g are uint16 arrays of bfloat16 / binary16 patterns."""
+    step = oracle.adam8bit_step_bf16 if bf16 else (oracle.adam8bit_step_f16 if f16 else oracle.adam8bit_step)
     qs, qu = codebooks()
     n = w.size
     nb = oracle.nblocks(n, B)
@@ -69,9 +69,9 @@ def oracle_adam8(w, g, st, B, wd=0.0, t=1, flags=0, hp=ADAM, split=True, bf16=Fa
     list(pool().map(run, range(nthr)))
 
 
-def oracle_sgd8(w, g, st, B, wd=0.0, hp=SGD, bf16=False):
+def oracle_sgd8(w, g, st, B, wd=0.0, hp=SGD, bf16=False, f16=False):
     qs, _ = codebooks()
-    step = oracle.sgd8bit_step_bf16 if bf16 else oracle.sgd8bit_step
+    step = oracle.sgd8bit_step_bf16 if bf16 else (oracle.sgd8bit_step_f16 if f16 else oracle.sgd8bit_step)
     step(w, g, st["m_q"], st["N_m"], qs, B, hp["alpha"], hp["beta"], wd)
 
 

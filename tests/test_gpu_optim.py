@@ -31,7 +31,7 @@ def make_model(dtype):
 
 
 def bits(t):
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):
         return t.detach().view(torch.int16).cpu().numpy().view(np.uint16).ravel()
     return t.detach().cpu().numpy().ravel()
 
@@ -39,8 +39,9 @@ def bits(t):
 class Ref:
     """Per-tensor oracle state mirroring the optimizer's choices (8-bit from min8 elements on)."""
 
-    def __init__(self, model, B, adam, min8, bf16):
-        self.B, self.adam, self.bf16 = B, adam, bf16
+    def __init__(self, model, B, adam, min8, store):
+        self.B, self.adam, self.store = B, adam, store          # store: "f32", "bf16" or "f16"
+        self.bf16, self.f16 = store == "bf16", store == "f16"
         self.t = []
         for p in model.parameters():
             n = p.numel()
@@ -54,27 +55,35 @@ class Ref:
     def step(self, grads, t, hp):
         for e, g in zip(self.t, grads):
             if e["small"]:
-                w32 = (e["w"].astype(np.uint32) << 16).view(np.float32) if self.bf16 else e["w"]
-                g32 = (g.astype(np.uint32) << 16).view(np.float32) if self.bf16 else g
+                w32, g32 = self.widen(e["w"]), self.widen(g)
                 if self.adam:
                     oracle.adam32_step(w32, g32, e["m"], e["r"], hp["alpha"], hp["beta1"], hp["beta2"], hp["eps"],
                                        hp["wd"], t, hp["flags"])
                 else:
                     oracle.sgd32_step(w32, g32, e["m"], hp["alpha"], hp["beta"], hp["wd"])
-                if self.bf16:
-                    e["w"][:] = np.array([oracle.f32_to_bf16(v) for v in w32], np.uint16)
+                if self.store != "f32":
+                    narrow = oracle.f32_to_bf16 if self.bf16 else oracle.f32_to_f16
+                    e["w"][:] = np.array([narrow(v) for v in w32], np.uint16)
             elif self.adam:
                 H.oracle_adam8(e["w"], g, e["st"], self.B, wd=hp["wd"], t=t, flags=hp["flags"],
                                hp=dict(alpha=hp["alpha"], beta1=hp["beta1"], beta2=hp["beta2"], eps=hp["eps"]),
-                               bf16=self.bf16)
+                               bf16=self.bf16, f16=self.f16)
             else:
                 H.oracle_sgd8(e["w"], g, e["st"], self.B, wd=hp["wd"], hp=dict(alpha=hp["alpha"], beta=hp["beta"]),
-                              bf16=self.bf16)
+                              bf16=self.bf16, f16=self.f16)
+
+    def widen(self, a):
+        if self.bf16:
+            return (a.astype(np.uint32) << 16).view(np.float32)
+        if self.f16:
+            return a.view(np.float16).astype(np.float32)
+        return a
 
     def check(self, model, opt, tag):
         for i, (e, p) in enumerate(zip(self.t, model.parameters())):
             got = bits(p)
-            same = (got.view(np.uint16 if self.bf16 else np.uint32) == e["w"].view(np.uint16 if self.bf16 else np.uint32))
+            u = np.uint32 if self.store == "f32" else np.uint16
+            same = got.view(u) == e["w"].view(u)
             assert same.all(), "%s tensor %d: %d weights differ" % (tag, i, int((~same).sum()))
             st = opt.state[p]
             if e["small"]:
@@ -97,11 +106,11 @@ def train_step(model, opt, x):
     return grads
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
 @pytest.mark.parametrize("kind", ["adam", "adamw", "sgd"])
 def test_optimizer_matches_oracle_and_survives_checkpoint(optim, dtype, kind):
     B, min8 = 256, 4096
-    bf16 = dtype == torch.bfloat16
+    store = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}[dtype]
     model = make_model(dtype)
     if kind == "sgd":
         opt = optim.SGD8bit(model.parameters(), lr=0.05, momentum=0.9, weight_decay=1e-4, block_size=B, min_8bit_size=min8)
@@ -114,7 +123,7 @@ def test_optimizer_matches_oracle_and_survives_checkpoint(optim, dtype, kind):
                              decoupled_weight_decay=True, block_size=B, min_8bit_size=min8)
         hp = dict(alpha=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, wd=0.05,
                   flags=oracle.FLAG_BIAS_CORRECTION | oracle.FLAG_DECOUPLED_WD)
-    ref = Ref(model, B, kind != "sgd", min8, bf16)
+    ref = Ref(model, B, kind != "sgd", min8, store)
     gen = torch.Generator(device="cuda"); gen.manual_seed(11)
     for t in range(1, 5):
         x = torch.randn(32, 64, device="cuda", generator=gen).to(dtype)
@@ -142,7 +151,7 @@ def test_optimizer_matches_oracle_and_survives_checkpoint(optim, dtype, kind):
 
 
 def test_optimizer_rejects_what_it_cannot_run(optim):
-    p = torch.nn.Parameter(torch.zeros(100, dtype=torch.float16, device="cuda"))
+    p = torch.nn.Parameter(torch.zeros(100, dtype=torch.float64, device="cuda"))
     opt = optim.Adam8bit([p])
     p.grad = torch.zeros_like(p)
     with pytest.raises(RuntimeError):
