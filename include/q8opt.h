@@ -187,7 +187,10 @@ Q8_API q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t* m_
                               float alpha, float beta, float weight_decay, void* stream);
 
 /*
- * Multi-tensor launch: one kernel launch updates a whole list of parameter
+ * Multi-tensor launch: the networks of Sec. V-B / Sec. VI-B (ResNets and RevNets
+ * under SGD with momentum, DF-ResNets and DF-RevNets under AdamW) hold hundreds
+ * of parameter tensors, each chunked on its own (Sec. IV-B, block-wise
+ * quantization); one kernel launch updates a whole list of parameter
  * tensors (blocks never span tensors).  A tensor with m_f32 != NULL keeps
  * 32-bit states (m_f32, and r_f32 for Adam; same update formulas, no
  * quantization; m_q/r_q/N_m/N_r ignored); otherwise it uses 8-bit states.
