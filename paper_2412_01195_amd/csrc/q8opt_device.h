@@ -1,0 +1,1216 @@
+// Device code of the fused 8-bit optimizer step for gfx950, shared by the translation units
+// of the library (one per storage type of w and g, so that they compile in parallel).
+//
+// Work decomposition: one wave64 owns 1024 consecutive elements of one tensor, read
+// as 4 rows of 256 elements; lane l of the wave holds elements [256 r + 4 l,
+// 256 r + 4 l + 4) of row r, so every fp32 access is one coalesced 128-bit
+// load/store per lane and every code access one coalesced 32-bit one.  New states
+// stay in registers between the update and the re-quantization, so HBM is touched
+// once per byte.  The block absmax is reduced with DPP steps inside the wave; for
+// B <= 1024 a wave holds whole blocks, for B = 2048 (4096) the 2 (4) waves that
+// share a block exchange their maxima through LDS with one barrier.
+//
+// Scheduling: workgroups of 8 waves are persistent.  They stage the search tables
+// into 64 KB of LDS once and then draw "jobs" of 8 consecutive wave tiles from an
+// atomic counter in device memory.  Handing work out in address order to whichever
+// workgroup is free keeps the set of addresses in flight one dense, slowly
+// advancing window over each stream, which is what the HBM controllers reward: on
+// a bandwidth skeleton of this access pattern a static grid-stride assignment
+// reached 5.1 TB/s, chunks 5.4 TB/s, dynamic jobs of 8 x 2048 elements 5.9 TB/s and
+// dynamic jobs of 8 x 1024 elements (half the window) 6.4 TB/s.
+//
+// Barriers sit in wave-uniform branches: the waves of a workgroup may reach their
+// one exchange barrier of a job at different program points (full tile, ragged
+// tile, no tile), which is sound on this hardware because s_barrier only counts
+// arriving waves; every wave executes the same number of barriers per job.
+//
+// Nearest-code search (Eq. quant2): the upper 16 bits of the binary32 pattern of
+// x = m / N index a byte table in LDS that holds the code at the lower end of that
+// bucket; one threshold read and one compare finish the decision exactly.
+//
+// Exact arithmetic: the update formulas are written one operation per statement
+// and the file is compiled with -ffp-contract=off.  The normalisation x = m / N
+// (Eq. quant1) is a correctly rounded quotient: N is uniform over a block, so
+// y = RN(1/N) is formed once and each element takes a faithful product and one
+// residual-correction fma pair (the classical Newton/Markstein division
+// sequence); blocks whose N lies outside [2^-60, 2^60] use the plain divide.  The
+// square root and the division of the Adam weight update take short, equally exact
+// forms on rows whose new states all lie in [2^-80, 2^40], sqrtf and a / b otherwise.
+//
+// Storage type: weights and gradients are binary32, bfloat16 or binary16 (template
+// parameter WT of the step kernels); the arithmetic and the 8-bit states are the same.
+#ifndef Q8OPT_DEVICE_H
+#define Q8OPT_DEVICE_H
+
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+
+#include <atomic>
+
+#include "q8opt.h"
+#include "q8opt_internal.h"
+
+namespace q8 {
+
+// ---------------------------------------------------------------------------
+// Types and functions shared between the translation units of the library.
+// ---------------------------------------------------------------------------
+struct TensorDesc {                       // device-side mirror of q8_tensor
+    void* w;                              // float or bfloat16 elements: fixed by the kernel's WT
+    const void* g;
+    uint8_t* m_q;
+    uint8_t* r_q;
+    float* N_m;
+    float* N_r;
+    float* m_f32;
+    float* r_f32;
+    int64_t n;
+};
+
+struct TileRef { int32_t tensor; int32_t tile; };
+
+struct AdamScalars {
+    float beta1, beta2, omb1, omb2, eps, wd, alpha_t, isbc2, alpha_wd;
+    int wd_mode;                          // 0 none, 1 coupled (g += wd*w), 2 decoupled
+    int fast_ok;                          // eps and isbc2 allow the short square root / division
+};
+struct SgdScalars { float alpha, beta, wd; };
+
+// Job counter of the dynamic scheduler (see "Dynamic scheduling" below).
+struct Sched { unsigned long long next, done; };
+
+struct StepArgs {
+    const TensorDesc* descs;      // device list, or nullptr: use `single`
+    const TileRef* tiles;         // device unit table for lists, else nullptr
+    TensorDesc single;
+    int64_t nunits;
+    const void* qtab_s;
+    const void* qtab_u;
+    Sched* sched;
+};
+
+struct DeviceInfo { int cus; Sched* sched; };
+
+// Defined once, in q8opt_kernels.hip: the current device's CU count and the address of its
+// ring of job counters; the next counter of the ring.
+q8_status device_info(DeviceInfo& out);
+Sched* next_sched_slot(const DeviceInfo& di);
+
+// Everything below has internal linkage: each translation unit instantiates only the
+// kernels it launches.
+namespace {
+
+#ifndef Q8_WG_THREADS
+#define Q8_WG_THREADS 512
+#endif
+#ifndef Q8_MIN_WAVES
+#define Q8_MIN_WAVES 4
+#endif
+constexpr int kWgThreads = Q8_WG_THREADS;
+constexpr int kWavesPerWg = kWgThreads / 64;
+constexpr int kRow = 256;                 // elements per wave row: 64 lanes x 4
+
+// Pointers into HBM carry the global address space so that loads and stores
+// are global_* instructions (a generic pointer would make them flat_*).
+#define Q8_GLOBAL __attribute__((address_space(1)))
+typedef Q8_GLOBAL float gfloat;
+typedef Q8_GLOBAL const float gcfloat;
+typedef Q8_GLOBAL uint8_t gbyte;
+typedef Q8_GLOBAL const uint8_t gcbyte;
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef Q8_GLOBAL v4f gfloat4;
+typedef Q8_GLOBAL const v4f gcfloat4;
+typedef Q8_GLOBAL uint32_t gu32;
+typedef Q8_GLOBAL const uint32_t gcu32;
+typedef Q8_GLOBAL const v4u gcuint4;
+typedef Q8_GLOBAL uint16_t gu16;
+typedef Q8_GLOBAL const uint16_t gcu16;
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+typedef Q8_GLOBAL v2u gv2u;
+typedef Q8_GLOBAL const v2u gcv2u;
+
+
+
+
+// ---------------------------------------------------------------------------
+// LDS map (64 KB per workgroup).  The bucket table is indexed by the upper half
+// of a binary32 pattern: keys of x in [0, 1] are 0 .. 0x3F80 and keys of x in
+// [-1, -0] are 0x8000 .. 0xBF80, which leaves two holes.  The first hole hosts
+// the non-negative half of the second table (used for the state r >= 0), the
+// second one the two codebooks and threshold arrays.  Every 16-bit key, also
+// that of a NaN, stays inside the 64 KB.
+// ---------------------------------------------------------------------------
+constexpr int kLdsBytes = 0x10000;
+constexpr int kLutHalf = 0x3F90;          // bytes staged per half: keys 0 .. 0x3F8F
+constexpr int kLdsNeg = 0x8000;           // keys of negative x
+constexpr int kLdsU = 0x3F90;             // second table, keys of x >= 0
+constexpr int kLdsQ1 = 0xC000;            // first table: codebook, then thresholds
+constexpr int kLdsT1 = 0xC400;
+constexpr int kLdsQ2 = 0xC800;            // second table
+constexpr int kLdsT2 = 0xCC00;
+static_assert(kLdsU + kLutHalf <= kLdsNeg && kLdsNeg + kLutHalf <= kLdsQ1 && kLdsT2 + 1024 <= kLdsBytes, "LDS map");
+
+__device__ __forceinline__ void copy16(unsigned char* dst, const unsigned char* src, int bytes, int tid)
+{
+    gcuint4* s4 = (gcuint4*)src;
+    v4u* d4 = reinterpret_cast<v4u*>(dst);
+    for (int i = tid; i < bytes / 16; i += kWgThreads) d4[i] = s4[i];
+}
+
+// first table: both signs
+__device__ __forceinline__ void stage_first(unsigned char* lds, const void* qtab, int tid)
+{
+    const unsigned char* blob = static_cast<const unsigned char*>(qtab);
+    copy16(lds, blob + kOffLut, kLutHalf, tid);
+    copy16(lds + kLdsNeg, blob + kOffLut + 0x8000, kLutHalf, tid);
+    copy16(lds + kLdsQ1, blob + kOffQmap, 2048, tid);
+}
+
+// second table: non-negative half only
+__device__ __forceinline__ void stage_second(unsigned char* lds, const void* qtab, int tid)
+{
+    const unsigned char* blob = static_cast<const unsigned char*>(qtab);
+    copy16(lds + kLdsU, blob + kOffLut, kLutHalf, tid);
+    copy16(lds + kLdsQ2, blob + kOffQmap, 2048, tid);
+}
+
+// Nearest code of x (Eq. quant2) by bucket lookup + one exact threshold compare.
+// SECOND selects the second table, whose inputs are non-negative.
+template <bool SECOND>
+__device__ __forceinline__ uint32_t nearest_code(const unsigned char* lds, float x)
+{
+    const uint32_t bits = __float_as_uint(x);
+    uint32_t c;
+    float t;
+    if (SECOND) {
+        c = lds[kLdsU + __builtin_amdgcn_ubfe(bits, 16, 15)];
+        t = *reinterpret_cast<const float*>(lds + kLdsT2 + 4 * c);
+    } else {
+        c = lds[bits >> 16];
+        t = *reinterpret_cast<const float*>(lds + kLdsT1 + 4 * c);
+    }
+    return c + ((x >= t) ? 1u : 0u);
+}
+
+template <bool SECOND>
+__device__ __forceinline__ float dequant(const unsigned char* lds, uint32_t code, float N)
+{
+    return *reinterpret_cast<const float*>(lds + (SECOND ? kLdsQ2 : kLdsQ1) + 4 * code) * N;
+}
+
+// ---------------------------------------------------------------------------
+// Cross-lane max of non-negative binary32 values held as bit patterns (the
+// unsigned-integer order of such patterns is their numeric order).
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_max_step(uint32_t v)
+{
+    uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, true);
+    return max(v, o);
+}
+
+// max over each aligned group of GROUP lanes, returned in every lane of the group
+template <int GROUP>
+__device__ __forceinline__ uint32_t group_max(uint32_t v, int lane)
+{
+    v = dpp_max_step<0xB1>(v);            // quad_perm [1,0,3,2]
+    v = dpp_max_step<0x4E>(v);            // quad_perm [2,3,0,1]
+    v = dpp_max_step<0x141>(v);           // row_half_mirror
+    v = dpp_max_step<0x140>(v);           // row_mirror: every lane has its 16-lane max
+    if (GROUP >= 32) {
+        uint32_t o = (uint32_t)__builtin_amdgcn_ds_bpermute((lane ^ 16) << 2, (int)v);
+        v = max(v, o);
+    }
+    if (GROUP >= 64) {
+        uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)v, 0);
+        uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)v, 32);
+        v = max(a, b);
+    }
+    return v;
+}
+
+// Correctly rounded a / N for a block-uniform N in [2^-60, 2^60], |a| <= N, with
+// y = RN(1/N) and ylo = RN(RN(1 - N y) y), so that y + ylo = 1/N to about 2^-46.
+// q = RN(a y + RN(a ylo)) is then a faithful quotient, and one residual correction
+// with the correctly rounded reciprocal returns RN(a/N) (Markstein's division
+// theorem).  When the quotient is below the normal range (|a/N| < 2^-126) the
+// result may be off in its last bits; such values lie far below the smallest
+// threshold and get the same code.  Checked on the CPU against true division on
+// 3e9 random and near-midpoint pairs.
+__device__ __forceinline__ float div_fast(float a, float N, float y, float ylo)
+{
+    float t = a * ylo;
+    float q = __builtin_fmaf(a, y, t);
+    float r = __builtin_fmaf(-q, N, a);
+    return __builtin_fmaf(r, y, q);
+}
+
+__device__ __forceinline__ float div_any(float a, float N)
+{
+    return (N == 0.0f) ? 0.0f : a / N;
+}
+
+struct BlockNorm { float N, y, ylo; bool fast; };
+
+__device__ __forceinline__ bool norm_in_fast_range(uint32_t nbits)
+{
+    return (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
+}
+
+// Reciprocal data of one block maximum held per lane (used when lanes of a wave
+// belong to different blocks, B < 256).
+__device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
+{
+    BlockNorm b;
+    b.N = __uint_as_float(nbits);
+    b.fast = norm_in_fast_range(nbits);
+    b.y = b.fast ? 1.0f / b.N : 0.0f;
+    const float e = __builtin_fmaf(-b.N, b.y, 1.0f);
+    b.ylo = e * b.y;
+    return b;
+}
+
+// Reciprocal data of K wave-uniform block maxima with ONE division sequence: the
+// K values are spread over lanes 0..K-1, divided there, and read back.
+template <int K>
+__device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm (&out)[K], int lane)
+{
+    int v = (int)nbits[0];
+#pragma unroll
+    for (int k = 1; k < K; ++k) v = (lane == k) ? (int)nbits[k] : v;
+    const float N = __int_as_float(v);
+    const float y = norm_in_fast_range((uint32_t)v) ? 1.0f / N : 0.0f;
+    const float e = __builtin_fmaf(-N, y, 1.0f);
+    const float ylo = e * y;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+        out[k].N = __uint_as_float(nbits[k]);
+        out[k].fast = norm_in_fast_range(nbits[k]);
+        out[k].y = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y), k));
+        out[k].ylo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ylo), k));
+    }
+}
+
+// Short forms of the square root and of the division in the Adam weight update,
+// used on rows where every new state lies in [kFastLo, kFastHi] (and the host has
+// found eps and the bias-correction factor within [0, 2^10] resp. [1, 2^10]); all
+// other rows take sqrtf and the general a / b.
+//
+// Square root: v_sqrt_f32 is within one ulp; the two neighbours are tested with fma
+// residuals, which are exact in this range: r - s_dn s <= 0 means sqrt(r) lies below
+// the midpoint of s_dn and s (the geometric mean of two neighbours is within a
+// quarter ulp^2 of their midpoint, closer than any binary32 r can come), likewise
+// for s_up.
+//
+// Division: for r in the range, d = fma(sqrt(r), c, eps) lies in [2^-40, 2^31] and
+// |m| / d in [2^-111, 2^80].  For such operands the compiler's correctly rounded
+// a / b -- v_div_scale, v_rcp, one reciprocal refinement, a product and two quotient
+// refinements, v_div_fmas, v_div_fixup -- scales nothing and fixes nothing up (no
+// operand or quotient is zero, subnormal or near the exponent limits, the exponents
+// differ by less than 96), so the same chain of fma without those three
+// instructions returns the same bits.
+constexpr float kFastLo = 0x1p-80f;
+constexpr float kFastHi = 0x1p40f;
+
+__device__ __forceinline__ float div_rn_inrange(float a, float b)
+{
+    float y = __builtin_amdgcn_rcpf(b);
+    const float e = __builtin_fmaf(-b, y, 1.0f);
+    y = __builtin_fmaf(e, y, y);
+    float q = a * y;
+    float r = __builtin_fmaf(-b, q, a);
+    q = __builtin_fmaf(r, y, q);
+    r = __builtin_fmaf(-b, q, a);
+    return __builtin_fmaf(r, y, q);
+}
+
+__device__ __forceinline__ float sqrt_rn_fast(float r)
+{
+    const float s = __builtin_amdgcn_sqrtf(r);
+    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
+    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
+    const float e_dn = __builtin_fmaf(-s_dn, s, r);
+    const float e_up = __builtin_fmaf(-s_up, s, r);
+    float out = (e_dn <= 0.0f) ? s_dn : s;
+    out = (e_up > 0.0f) ? s_up : out;
+    return out;
+}
+
+// ---------------------------------------------------------------------------
+// Per-lane row access.  cnt = number of valid elements (0..4) of this lane in
+// the row; FULL tiles have cnt == 4 everywhere.  The bulk data is touched once
+// per step, so full-width accesses carry the non-temporal hint.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int lane_count(int64_t n, int64_t e0)
+{
+    int64_t left = n - e0;
+    return left >= 4 ? 4 : (left <= 0 ? 0 : (int)left);
+}
+
+// Running maximum of |x| over a lane's elements, kept as the bit pattern of a
+// non-negative float (finite inputs: the order of such floats is the order of their
+// bit patterns).  Written as a float maximum so that it compiles to v_max3_f32 with
+// |.| source modifiers, two elements per instruction.
+__device__ __forceinline__ uint32_t absmax4(uint32_t acc, const float (&v)[4])
+{
+    float a = __uint_as_float(acc);
+    a = __builtin_fmaxf(__builtin_fmaxf(a, __builtin_fabsf(v[0])), __builtin_fabsf(v[1]));
+    a = __builtin_fmaxf(__builtin_fmaxf(a, __builtin_fabsf(v[2])), __builtin_fabsf(v[3]));
+    return __float_as_uint(a);
+}
+
+__device__ __forceinline__ void load4f(gcfloat* p, int cnt, float (&v)[4])
+{
+    if (cnt == 4) {
+        const v4f t = __builtin_nontemporal_load((gcfloat4*)p);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = (j < cnt) ? p[j] : 0.0f;
+    }
+}
+
+__device__ __forceinline__ void store4f(gfloat* p, int cnt, const float (&v)[4])
+{
+    if (cnt == 4) {
+        const v4f t = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(t, (gfloat4*)p);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < cnt) p[j] = v[j];
+    }
+}
+
+__device__ __forceinline__ uint32_t load4b(gcbyte* p, int cnt)
+{
+    if (cnt == 4) return __builtin_nontemporal_load((gcu32*)p);
+    uint32_t v = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        if (j < cnt) v |= (uint32_t)p[j] << (8 * j);
+    return v;
+}
+
+__device__ __forceinline__ void store4b(gbyte* p, int cnt, uint32_t v)
+{
+    if (cnt == 4) {
+        __builtin_nontemporal_store(v, (gu32*)p);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (j < cnt) p[j] = (uint8_t)(v >> (8 * j));
+    }
+}
+
+// Storage type WT of weights and gradients: float, Bf16 (bfloat16 = the upper half of
+// a binary32) or F16 (IEEE binary16).  Widening is exact; narrowing is the hardware's
+// round-to-nearest-even conversion (v_cvt_pk_bf16_f32 / v_cvt_pk_f16_f32, binary16
+// subnormals kept), applied once to the new weight.
+struct Bf16 { uint16_t bits; };
+struct F16 { uint16_t bits; };
+
+template <typename WT> struct Wide;
+template <> struct Wide<float> { typedef gfloat* ptr; typedef gcfloat* cptr; };
+template <> struct Wide<Bf16> { typedef gu16* ptr; typedef gcu16* cptr; };
+template <> struct Wide<F16> { typedef gu16* ptr; typedef gcu16* cptr; };
+
+template <typename WT> __device__ __forceinline__ void widen2(uint32_t pair, float& lo, float& hi);
+template <> __device__ __forceinline__ void widen2<Bf16>(uint32_t pair, float& lo, float& hi)
+{
+    lo = __uint_as_float(pair << 16);
+    hi = __uint_as_float(pair & 0xffff0000u);
+}
+template <> __device__ __forceinline__ void widen2<F16>(uint32_t pair, float& lo, float& hi)
+{
+    const v2f f = __builtin_convertvector(__builtin_bit_cast(v2h, pair), v2f);
+    lo = f.x;
+    hi = f.y;
+}
+
+template <typename WT> __device__ __forceinline__ uint32_t narrow2(float lo, float hi);
+template <> __device__ __forceinline__ uint32_t narrow2<Bf16>(float lo, float hi)
+{
+    const v2f x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, v2bf));
+}
+template <> __device__ __forceinline__ uint32_t narrow2<F16>(float lo, float hi)
+{
+    const v2f x = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, v2h));
+}
+
+template <typename WT>
+__device__ __forceinline__ void load4w(gcfloat* p, int cnt, float (&v)[4]) { load4f(p, cnt, v); }
+template <typename WT>
+__device__ __forceinline__ void store4w(gfloat* p, int cnt, const float (&v)[4]) { store4f(p, cnt, v); }
+
+template <typename WT>
+__device__ __forceinline__ void load4w(gcu16* p, int cnt, float (&v)[4])
+{
+    uint32_t a, b;
+    if (cnt == 4) {
+        const v2u t = __builtin_nontemporal_load((gcv2u*)p);
+        a = t.x;
+        b = t.y;
+    } else {
+        uint32_t h[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) h[j] = (j < cnt) ? (uint32_t)p[j] : 0u;
+        a = h[0] | (h[1] << 16);
+        b = h[2] | (h[3] << 16);
+    }
+    widen2<WT>(a, v[0], v[1]);
+    widen2<WT>(b, v[2], v[3]);
+}
+
+template <typename WT>
+__device__ __forceinline__ void store4w(gu16* p, int cnt, const float (&v)[4])
+{
+    const uint32_t a = narrow2<WT>(v[0], v[1]), b = narrow2<WT>(v[2], v[3]);
+    if (cnt == 4) {
+        const v2u t = {a, b};
+        __builtin_nontemporal_store(t, (gv2u*)p);
+    } else {
+        if (cnt > 0) p[0] = (uint16_t)a;
+        if (cnt > 1) p[1] = (uint16_t)(a >> 16);
+        if (cnt > 2) p[2] = (uint16_t)b;
+    }
+}
+
+// Geometry.  A wave owns 1024 consecutive elements (4 rows).  A "unit" is
+// max(B, 1024) elements: the granule of the tile table and of scheduling.  For
+// B <= 1024 a unit is one wave and holds 1024/B whole blocks; for B = 2048 (4096)
+// the 2 (4) waves of a unit share one block and exchange their maxima through LDS.
+constexpr int kWaveRows = 4;
+constexpr int kWaveElems = kWaveRows * kRow;
+
+template <int B>
+struct Shape {
+    static constexpr int UNIT = (B > kWaveElems) ? B : kWaveElems;
+    static constexpr int WPB = UNIT / kWaveElems;                       // waves per unit: 1, 2, 4
+    static constexpr int UPJ = kWavesPerWg / WPB;                       // units per job
+    static constexpr int RPB = (B >= kWaveElems) ? kWaveRows : (B >= kRow ? B / kRow : 1);   // rows per block slot
+    static constexpr int GROUP = (B >= kRow) ? 64 : B / 4;              // lanes per block in a row
+    static constexpr int NBLK = kWaveRows / RPB;                        // block slots per lane
+};
+
+// Block maxima of NSTATE states x NBLK slots -> reciprocal data.
+template <int B, int NSTATE>
+__device__ __forceinline__ void norms_of(const uint32_t (&nbits)[NSTATE][Shape<B>::NBLK],
+                                         BlockNorm (&out)[NSTATE][Shape<B>::NBLK], int lane)
+{
+    using S = Shape<B>;
+    if (S::GROUP == 64) {
+        uint32_t flat[NSTATE * S::NBLK];
+        BlockNorm bn[NSTATE * S::NBLK];
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) flat[st * S::NBLK + k] = nbits[st][k];
+        make_norms<NSTATE * S::NBLK>(flat, bn, lane);
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) out[st][k] = bn[st * S::NBLK + k];
+    } else {
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) out[st][k] = make_norm(nbits[st][k]);
+    }
+}
+
+// LDS words for the exchange of wave maxima: [parity][state][wave].
+struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
+
+// Turn lane maxima into block maxima: DPP reduction inside the wave and, when a
+// block spans WPB > 1 waves, an exchange through LDS.  In that case every wave of
+// the workgroup must call this exactly once per job (it contains a barrier);
+// `parity` alternates between jobs so that one barrier per job suffices: a slot
+// is rewritten two jobs later, after barriers that every reader has passed.
+template <int B, int NSTATE>
+__device__ __forceinline__ void reduce_block_max(uint32_t (&v)[NSTATE][Shape<B>::NBLK], Exchange* ex, int parity,
+                                                 int wave, int lane)
+{
+    using S = Shape<B>;
+#pragma unroll
+    for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+        for (int k = 0; k < S::NBLK; ++k) v[st][k] = group_max<S::GROUP>(v[st][k], lane);
+    if (S::WPB > 1) {
+        if (lane == 0) {
+#pragma unroll
+            for (int st = 0; st < NSTATE; ++st) ex->part[parity][st][wave] = v[st][0];
+        }
+        __syncthreads();
+        const int g0 = wave & ~(S::WPB - 1);
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st) {
+            uint32_t m = 0;
+#pragma unroll
+            for (int k = 0; k < S::WPB; ++k) m = max(m, ex->part[parity][st][g0 + k]);
+            v[st][0] = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
+        }
+    }
+}
+
+// The barrier of reduce_block_max for waves that have no 8-bit tile in this job.
+template <int B>
+__device__ __forceinline__ void idle_block_max()
+{
+    if (Shape<B>::WPB > 1) __syncthreads();
+}
+
+// Quantize the 4 x 4 values of this lane (Eq. quant1, quant2) against the block
+// maxima (with their reciprocal data, one entry per block slot) and store codes and maxima.
+// `base` is the first element of this wave, `part` its index inside the unit.
+template <int B, bool FULL, bool SECOND>
+__device__ __forceinline__ void requantize_store(const unsigned char* lds, float (&val)[kWaveRows][4],
+                                                 const BlockNorm (&norms)[Shape<B>::NBLK],
+                                                 gbyte* codes, gfloat* Nout,
+                                                 int64_t n, int64_t base, int part, int lane)
+{
+    using S = Shape<B>;
+#pragma unroll
+    for (int s = 0; s < S::NBLK; ++s) {
+        const BlockNorm bn = norms[s];
+        const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
+        if (B >= kRow) {
+            if (part == 0 && lane == 0 && (FULL || row0 < n)) Nout[row0 / B] = bn.N;
+        } else {
+            const int64_t e0 = row0 + lane * 4;
+            if ((lane % S::GROUP) == 0 && (FULL || e0 < n)) Nout[e0 / B] = bn.N;
+        }
+        // one wave-uniform decision per block slot keeps the common path straight-line
+        const bool all_fast = (S::GROUP == 64) ? bn.fast : (__builtin_amdgcn_ballot_w64(!bn.fast) == 0);
+        if (all_fast) {
+#pragma unroll
+            for (int rr = 0; rr < S::RPB; ++rr) {
+                const int r = s * S::RPB + rr;
+                const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+                const int cnt = FULL ? 4 : lane_count(n, e0);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    packed |= nearest_code<SECOND>(lds, div_fast(val[r][j], bn.N, bn.y, bn.ylo)) << (8 * j);
+                if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+            }
+        } else {
+#pragma unroll
+            for (int rr = 0; rr < S::RPB; ++rr) {
+                const int r = s * S::RPB + rr;
+                const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+                const int cnt = FULL ? 4 : lane_count(n, e0);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    packed |= nearest_code<SECOND>(lds, div_any(val[r][j], bn.N)) << (8 * j);
+                if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
+            }
+        }
+    }
+}
+
+// Old block maximum for row r of this wave.  For B >= 256 the index is wave-uniform
+// and the value is read with a scalar load: the entry was written by an earlier
+// launch (or, later in this launch, only by a wave of this very unit after the
+// barrier), so the scalar cache cannot hold a stale copy.  Below 256 each lane
+// group reads its own block.
+#define Q8_CONSTANT __attribute__((address_space(4)))
+template <int B, bool FULL>
+__device__ __forceinline__ float load_block_max(const float* N, int64_t n, int64_t base, int r, int lane)
+{
+    const int64_t row0 = base + (int64_t)r * kRow;
+    if (B >= kRow) {
+        if (!FULL && row0 >= n) return 0.0f;
+        return ((Q8_CONSTANT const float*)N)[row0 / B];
+    }
+    const int64_t e0 = row0 + lane * 4;
+    if (!FULL && e0 >= n) return 0.0f;
+    return ((gcfloat*)N)[e0 / B];
+}
+
+// ---------------------------------------------------------------------------
+// Element arithmetic (one statement = one rounded binary32 operation).
+// ---------------------------------------------------------------------------
+// New states of Eq. adam.  g is updated in place when coupled decay applies.
+template <int WD>
+__device__ __forceinline__ void adam_states(const AdamScalars& s, float w, float g, float m_prev, float r_prev,
+                                            float& m_out, float& r_out)
+{
+    if (WD == 1) {
+        float t0 = s.wd * w;
+        g = g + t0;
+    }
+    float t1 = s.beta1 * m_prev;
+    float t2 = s.omb1 * g;
+    m_out = t1 + t2;
+    float t3 = s.beta2 * r_prev;
+    float t4 = s.omb2 * g;
+    float t5 = t4 * g;
+    r_out = t3 + t5;
+}
+
+// Weight update of Eq. adam from the new 32-bit states.  FAST selects the short
+// square root and division, valid when the caller has checked the range of m and r.
+template <int WD, bool FAST>
+__device__ __forceinline__ float adam_weight(const AdamScalars& s, float w, float m, float r)
+{
+    const float root = FAST ? sqrt_rn_fast(r) : sqrtf(r);
+    // without bias correction isbc2 == 1 and the fma is exactly root + eps; with it the
+    // denominator is defined as this single fused operation
+    const float d = __builtin_fmaf(root, s.isbc2, s.eps);
+    const float u = FAST ? div_rn_inrange(m, d) : m / d;
+    const float t6 = s.alpha_t * u;
+    if (WD == 2) {
+        float t7 = s.alpha_wd * w;
+        w = w - t7;
+    }
+    return w - t6;
+}
+
+template <int WD>
+__device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, float g, float m_prev,
+                                             float r_prev, float& m_out, float& r_out)
+{
+    float m, r;
+    adam_states<WD>(s, w, g, m_prev, r_prev, m, r);
+    w = adam_weight<WD, false>(s, w, m, r);
+    m_out = m;
+    r_out = r;
+}
+
+template <bool WD>
+__device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float g, float m_prev, float& m_out)
+{
+    float wv = w;
+    if (WD) {
+        float t0 = s.wd * wv;
+        g = g + t0;
+    }
+    float t1 = s.beta * m_prev;
+    float m = t1 + g;
+    float t2 = s.alpha * m;
+    w = wv - t2;
+    m_out = m;
+}
+
+// ---------------------------------------------------------------------------
+// Wave tiles.  `base` = first element of this wave inside the tensor.
+// ---------------------------------------------------------------------------
+template <int B, typename WT, bool FULL, int WD>
+__device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
+                                           Exchange* ex, int parity, const AdamScalars& sc, int wave, int lane)
+{
+    using S = Shape<B>;
+    const int64_t n = d.n;
+    typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
+    typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
+    gbyte* m_q = (gbyte*)d.m_q;
+    gbyte* r_q = (gbyte*)d.r_q;
+    float wv[kWaveRows][4], gv[kWaveRows][4];
+    uint32_t mq[kWaveRows], rq[kWaveRows];
+    float Nm_old[kWaveRows], Nr_old[kWaveRows];
+#pragma unroll
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = FULL ? 4 : lane_count(n, e0);
+        if (FULL || cnt > 0) {
+            load4w<WT>(w + e0, cnt, wv[r]);
+            load4w<WT>(g + e0, cnt, gv[r]);
+            mq[r] = load4b(m_q + e0, cnt);
+            rq[r] = load4b(r_q + e0, cnt);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
+            mq[r] = 0; rq[r] = 0;
+        }
+        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
+        Nr_old[r] = load_block_max<B, FULL>(d.N_r, n, base, r, lane);
+    }
+    uint32_t amax[2][S::NBLK];
+#pragma unroll
+    for (int s = 0; s < S::NBLK; ++s) { amax[0][s] = 0; amax[1][s] = 0; }
+    // after this loop gv holds the new m and wv is reused for the new r
+#pragma unroll
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = FULL ? 4 : lane_count(n, e0);
+        float mnew[4], rnew[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
+            const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[r]);
+            adam_states<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, mnew[j], rnew[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
+        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], mnew);
+        amax[1][r / S::RPB] = absmax4(amax[1][r / S::RPB], rnew);
+        // one wave-uniform test per row: every |m| and r of the row within [kFastLo, kFastHi]
+        // (the running maxima bound the row from above; a row that holds an exact zero,
+        // e.g. in a ragged tail, takes the general forms)
+        float lo = __builtin_fminf(__builtin_fminf(__builtin_fabsf(mnew[0]), __builtin_fabsf(mnew[1])), __builtin_fabsf(mnew[2]));
+        lo = __builtin_fminf(__builtin_fminf(lo, __builtin_fabsf(mnew[3])), rnew[0]);
+        lo = __builtin_fminf(__builtin_fminf(lo, rnew[1]), rnew[2]);
+        lo = __builtin_fminf(lo, rnew[3]);
+        const float hi = __builtin_fmaxf(__uint_as_float(amax[0][r / S::RPB]), __uint_as_float(amax[1][r / S::RPB]));
+        const bool general = !(lo >= kFastLo) || !(hi <= kFastHi) || !sc.fast_ok;
+        if (__builtin_amdgcn_ballot_w64(general) == 0) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, true>(sc, wv[r][j], mnew[j], rnew[j]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, false>(sc, wv[r][j], mnew[j], rnew[j]);
+        }
+        if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            gv[r][j] = mnew[j];
+            wv[r][j] = rnew[j];
+        }
+    }
+    reduce_block_max<B, 2>(amax, ex, parity, wave, lane);
+    BlockNorm bn[2][S::NBLK];
+    norms_of<B, 2>(amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, gv, bn[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
+    requantize_store<B, FULL, true>(lds, wv, bn[1], r_q, (gfloat*)d.N_r, n, base, part, lane);
+}
+
+template <int B, typename WT, bool FULL, bool WD>
+__device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
+                                          Exchange* ex, int parity, const SgdScalars& sc, int wave, int lane)
+{
+    using S = Shape<B>;
+    const int64_t n = d.n;
+    typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
+    typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
+    gbyte* m_q = (gbyte*)d.m_q;
+    float wv[kWaveRows][4], gv[kWaveRows][4];
+    uint32_t mq[kWaveRows];
+    float Nm_old[kWaveRows];
+#pragma unroll
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = FULL ? 4 : lane_count(n, e0);
+        if (FULL || cnt > 0) {
+            load4w<WT>(w + e0, cnt, wv[r]);
+            load4w<WT>(g + e0, cnt, gv[r]);
+            mq[r] = load4b(m_q + e0, cnt);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
+            mq[r] = 0;
+        }
+        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
+    }
+    uint32_t amax[1][S::NBLK];
+#pragma unroll
+    for (int s = 0; s < S::NBLK; ++s) amax[0][s] = 0;
+#pragma unroll
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = FULL ? 4 : lane_count(n, e0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
+            float m_new;
+            sgd_element<WD>(sc, wv[r][j], gv[r][j], m_prev, m_new);
+            if (!FULL && j >= cnt) m_new = 0.0f;
+            gv[r][j] = m_new;
+        }
+        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], gv[r]);
+        if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
+    }
+    reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
+    BlockNorm bn[1][S::NBLK];
+    norms_of<B, 1>(amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, gv, bn[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
+}
+
+// Tensors that keep 32-bit states: same formulas, no quantization; one wave
+// handles its 1024 elements.
+template <typename WT, bool ADAM>
+__device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, const AdamScalars& as,
+                                         const SgdScalars& ss, int lane)
+{
+    const int64_t n = d.n;
+    typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
+    typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
+    gfloat* m = (gfloat*)d.m_f32;
+    gfloat* rr = (gfloat*)d.r_f32;
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = lane_count(n, e0);
+        if (cnt == 0) continue;
+        float wv[4], gv[4], mv[4], rv[4] = {0.f, 0.f, 0.f, 0.f};
+        load4w<WT>(w + e0, cnt, wv);
+        load4w<WT>(g + e0, cnt, gv);
+        load4f(m + e0, cnt, mv);
+        if (ADAM) load4f(rr + e0, cnt, rv);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (ADAM) {
+                if (as.wd_mode == 1) adam_element<1>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                else if (as.wd_mode == 2) adam_element<2>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                else adam_element<0>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+            } else {
+                if (ss.wd != 0.0f) sgd_element<true>(ss, wv[j], gv[j], mv[j], mv[j]);
+                else sgd_element<false>(ss, wv[j], gv[j], mv[j], mv[j]);
+            }
+        }
+        store4w<WT>(w + e0, cnt, wv);
+        store4f(m + e0, cnt, mv);
+        if (ADAM) store4f(rr + e0, cnt, rv);
+    }
+}
+
+template <int B, bool FULL>
+__device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int64_t n, int64_t base, int part,
+                                           const unsigned char* lds, Exchange* ex, int parity, int wave, int lane)
+{
+    using S = Shape<B>;
+    float v[kWaveRows][4];
+    uint32_t amax[1][S::NBLK];
+#pragma unroll
+    for (int s = 0; s < S::NBLK; ++s) amax[0][s] = 0;
+#pragma unroll
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = FULL ? 4 : lane_count(n, e0);
+        if (FULL || cnt > 0) {
+            load4f(T + e0, cnt, v[r]);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
+        }
+        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], v[r]);
+    }
+    reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
+    BlockNorm bn[1][S::NBLK];
+    norms_of<B, 1>(amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, v, bn[0], TQ, N, n, base, part, lane);
+}
+
+// ---------------------------------------------------------------------------
+// Dynamic scheduling.  A job is kWavesPerWg consecutive wave tiles, i.e. UPJ
+// consecutive units.  Thread 0 of a workgroup draws job indices from
+// `sched->next` and publishes them through LDS (two slots used alternately, so one
+// barrier per draw suffices).  Every workgroup leaves the loop at its first
+// out-of-range draw, without having another atomic in flight; the last one to
+// leave (counted in `sched->done`) zeroes both counters, so the slot is ready for
+// the next launch that uses it.
+// ---------------------------------------------------------------------------
+
+struct JobBox { long long job[2]; };
+
+// One draw hands a workgroup SPAN consecutive jobs.  The first draw is issued at the
+// very start of the kernel, before the tables are staged, so that its latency hides
+// behind the staging.  With AHEAD the atomic of every following draw is issued as soon
+// as the current one has been read, which hides its latency too but lets every
+// workgroup hold a claim one draw ahead (a wider address window); the optimizer steps
+// measured faster without it, the light stand-alone quantizer faster with it.
+template <int SPAN>
+__device__ __forceinline__ void first_draw(Sched* sched, JobBox* box)
+{
+    if (threadIdx.x == 0)
+        box->job[0] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+}
+
+// `first` = this is the draw that first_draw has already issued (parity 0).
+template <int SPAN, bool AHEAD>
+__device__ __forceinline__ int64_t next_draw(Sched* sched, JobBox* box, int parity, int64_t njobs, bool first)
+{
+    if (!AHEAD && !first && threadIdx.x == 0)
+        box->job[parity] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    __syncthreads();
+    const long long j = box->job[parity];
+    const int lo = __builtin_amdgcn_readfirstlane((int)j);
+    const int hi = __builtin_amdgcn_readfirstlane((int)(j >> 32));
+    const int64_t job = ((int64_t)hi << 32) | (uint32_t)lo;
+    if (AHEAD && job < njobs && threadIdx.x == 0)
+        box->job[parity ^ 1] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    return job;
+}
+
+// A launch with no more draws' worth of jobs than workgroups gives every workgroup
+// exactly one draw: nobody needs to ask a second time.
+template <int SPAN>
+__device__ __forceinline__ bool single_draw(int64_t njobs)
+{
+    return njobs <= (int64_t)gridDim.x * SPAN;
+}
+
+__device__ __forceinline__ void leave(Sched* sched)
+{
+    if (threadIdx.x == 0) {
+        const unsigned long long before = atomicAdd(&sched->done, 1ULL);
+        if (before == gridDim.x - 1) {
+            atomicExch(&sched->next, 0ULL);
+            atomicExch(&sched->done, 0ULL);
+        }
+    }
+}
+
+
+// Unit -> (tensor descriptor, unit index inside the tensor).  The tables are read
+// through the constant address space with wave-uniform indices, i.e. by scalar
+// loads into SGPRs.
+__device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t u, int64_t& unit_in_tensor)
+{
+    if (a.tiles) {
+        Q8_CONSTANT const int32_t* ref = (Q8_CONSTANT const int32_t*)a.tiles + 2 * u;
+        const int ti = ref[0];
+        unit_in_tensor = ref[1];
+        Q8_CONSTANT const uint64_t* f = (Q8_CONSTANT const uint64_t*)(a.descs + ti);
+        TensorDesc d;
+        d.w = (void*)f[0];
+        d.g = (const void*)f[1];
+        d.m_q = (uint8_t*)f[2];
+        d.r_q = (uint8_t*)f[3];
+        d.N_m = (float*)f[4];
+        d.N_r = (float*)f[5];
+        d.m_f32 = (float*)f[6];
+        d.r_f32 = (float*)f[7];
+        d.n = (int64_t)f[8];
+        return d;
+    }
+    unit_in_tensor = u;
+    return a.single;
+}
+static_assert(sizeof(TensorDesc) == 72 && sizeof(TileRef) == 8, "descriptor layout");
+
+struct Lds {
+    unsigned char tab[kLdsBytes];
+    JobBox box;
+    Exchange ex;
+};
+
+constexpr int kStepSpan = 1;        // jobs per draw of the optimizer-step kernels
+constexpr int kQuantSpan = 4;       // the stand-alone quantizer does far less work per job
+
+template <int B, typename WT, int WD>
+__device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars& sc, Lds* lds)
+{
+    using S = Shape<B>;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
+    const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
+    SgdScalars none{};
+    const bool once = single_draw<kStepSpan>(njobs);
+    int xpar = 0;
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        if (once && !first) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs, first);
+        if (j0 >= njobs) break;
+        for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
+            const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
+            bool done = false;
+            if (u < a.nunits) {
+                int64_t ut;
+                const TensorDesc d = resolve(a, u, ut);
+                const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
+                if (d.m_f32) {
+                    f32_tile<WT, true>(d, base, sc, none, lane);
+                } else if (base + kWaveElems <= d.n) {
+                    adam8_tile<B, WT, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    done = true;
+                } else {
+                    adam8_tile<B, WT, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    done = true;
+                }
+            }
+            if (!done) idle_block_max<B>();
+        }
+    }
+}
+
+template <int B, typename WT>
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
+{
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kStepSpan>(a.sched, &lds.box);
+    stage_first(lds.tab, a.qtab_s, threadIdx.x);
+    stage_second(lds.tab, a.qtab_u, threadIdx.x);
+    __syncthreads();
+    if (sc.wd_mode == 0) adam8_walk<B, WT, 0>(a, sc, &lds);
+    else if (sc.wd_mode == 1) adam8_walk<B, WT, 1>(a, sc, &lds);
+    else adam8_walk<B, WT, 2>(a, sc, &lds);
+    leave(a.sched);
+}
+
+template <int B, typename WT, bool WD>
+__device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& sc, Lds* lds)
+{
+    using S = Shape<B>;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
+    const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
+    AdamScalars none{};
+    const bool once = single_draw<kStepSpan>(njobs);
+    int xpar = 0;
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        if (once && !first) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs, first);
+        if (j0 >= njobs) break;
+        for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
+            const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
+            bool done = false;
+            if (u < a.nunits) {
+                int64_t ut;
+                const TensorDesc d = resolve(a, u, ut);
+                const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
+                if (d.m_f32) {
+                    f32_tile<WT, false>(d, base, none, sc, lane);
+                } else if (base + kWaveElems <= d.n) {
+                    sgd8_tile<B, WT, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    done = true;
+                } else {
+                    sgd8_tile<B, WT, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
+                    done = true;
+                }
+            }
+            if (!done) idle_block_max<B>();
+        }
+    }
+}
+
+template <int B, typename WT>
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
+{
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kStepSpan>(a.sched, &lds.box);
+    stage_first(lds.tab, a.qtab_s, threadIdx.x);
+    __syncthreads();
+    if (sc.wd != 0.0f) sgd8_walk<B, WT, true>(a, sc, &lds);
+    else sgd8_walk<B, WT, false>(a, sc, &lds);
+    leave(a.sched);
+}
+
+template <int B>
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void quantize_kernel(const void* qtab, const float* T,
+                                                                              uint8_t* TQ, float* N, int64_t n,
+                                                                              int64_t nunits, Sched* sched)
+{
+    using S = Shape<B>;
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kQuantSpan>(sched, &lds.box);
+    stage_first(lds.tab, qtab, threadIdx.x);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
+    const int64_t njobs = (nunits + S::UPJ - 1) / S::UPJ;
+    int xpar = 0;
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        const int64_t j0 = next_draw<kQuantSpan, true>(sched, &lds.box, parity, njobs, first);
+        if (j0 >= njobs) break;
+        for (int k = 0; k < kQuantSpan && j0 + k < njobs; ++k, xpar ^= 1) {
+            const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
+            if (u < nunits) {
+                const int64_t base = u * S::UNIT + (int64_t)part * kWaveElems;
+                if (base + kWaveElems <= n)
+                    quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, &lds.ex, xpar, wave, lane);
+                else
+                    quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, &lds.ex, xpar, wave, lane);
+            } else {
+                idle_block_max<B>();
+            }
+        }
+    }
+    leave(sched);
+}
+
+// ---------------------------------------------------------------------------
+// Launch helpers (host).
+// ---------------------------------------------------------------------------
+
+// Persistent grid: enough workgroups to fill every CU to the kernel's
+// occupancy, never more than there are jobs.
+// `per_cu` caches the occupancy query of one kernel (0 = not asked yet; the
+// answer is the same on every device of one model, so one cache serves all).
+template <typename K>
+q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, int& grid, Sched** slot)
+{
+    DeviceInfo di;
+    q8_status st = device_info(di);
+    if (st != Q8_OK) return st;
+    int occ = per_cu.load(std::memory_order_relaxed);
+    if (occ <= 0) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kernel, kWgThreads, 0) != hipSuccess || occ <= 0)
+            return Q8_ELAUNCH;
+        per_cu.store(occ, std::memory_order_relaxed);
+    }
+    int64_t want = njobs;
+    int64_t cap = (int64_t)di.cus * occ;
+    grid = (int)(want < cap ? want : cap);
+    if (grid < 1) grid = 1;
+    *slot = next_sched_slot(di);
+    return Q8_OK;
+}
+
+inline q8_status launch_status()
+{
+    return hipGetLastError() == hipSuccess ? Q8_OK : Q8_ELAUNCH;
+}
+
+#define Q8_DISPATCH_B(B, CALL)                 \
+    switch (B) {                               \
+    case 64: { constexpr int kB = 64; CALL; } break;     \
+    case 128: { constexpr int kB = 128; CALL; } break;   \
+    case 256: { constexpr int kB = 256; CALL; } break;   \
+    case 512: { constexpr int kB = 512; CALL; } break;   \
+    case 1024: { constexpr int kB = 1024; CALL; } break; \
+    case 2048: { constexpr int kB = 2048; CALL; } break; \
+    case 4096: { constexpr int kB = 4096; CALL; } break; \
+    default: return Q8_EBLOCK;                 \
+    }
+
+template <int B, typename WT>
+q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
+{
+    static std::atomic<int> per_cu{0};
+    int grid;
+    q8_status st = grid_for(adam8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
+    if (st != Q8_OK) return st;
+    hipLaunchKernelGGL((adam8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
+    return launch_status();
+}
+
+template <int B, typename WT>
+q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
+{
+    static std::atomic<int> per_cu{0};
+    int grid;
+    q8_status st = grid_for(sgd8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
+    if (st != Q8_OK) return st;
+    hipLaunchKernelGGL((sgd8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
+    return launch_status();
+}
+
+template <int B>
+q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* N, int64_t n, hipStream_t stream)
+{
+    const int64_t nunits = (n + Shape<B>::UNIT - 1) / Shape<B>::UNIT;
+    static std::atomic<int> per_cu{0};
+    int grid;
+    Sched* slot = nullptr;
+    q8_status st = grid_for(quantize_kernel<B>, per_cu, (nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &slot);
+    if (st != Q8_OK) return st;
+    hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, nunits, slot);
+    return launch_status();
+}
+
+}  // namespace
+}  // namespace q8
+
+#endif  // Q8OPT_DEVICE_H
