@@ -347,3 +347,25 @@ def test_adam_gradient_scale_sweep_bitwise(q8, tabs, eps):
             got = w.cpu().numpy()
             same = (got.view(np.uint32) == w_ref.view(np.uint32)) | ((got == 0) & (w_ref == 0))
             assert same.all(), "decade %d step %d: %d weights differ in their bits" % (k, t, int((~same).sum()))
+
+
+@pytest.mark.parametrize("eps", [1e-8, 3e-3, 1.0, 700.0])
+def test_weight_update_quotient_bits(q8, tabs, eps):
+    """beta1 = beta2 = 0, alpha = 1, w = 0 turn the step into w = -(g / (sqrt(g*g) + eps)): four
+    million random numerators and denominators per eps, spread over the whole magnitude range
+    of the short division and square root, must give the oracle's (IEEE) bits."""
+    n, B = 1 << 22, 2048
+    rng = np.random.default_rng(int(eps * 1000) + 5)
+    mant = rng.integers(0, 1 << 23, n, dtype=np.uint64).astype(np.uint32)
+    expo = rng.integers(127 - 39, 127 + 19, n, dtype=np.uint64).astype(np.uint32)
+    sign = rng.integers(0, 2, n, dtype=np.uint64).astype(np.uint32)
+    g = ((sign << 31) | (expo << 23) | mant).view(np.float32)
+    hp = dict(alpha=1.0, beta1=0.0, beta2=0.0, eps=eps)
+    w_ref = np.zeros(n, np.float32)
+    st = H.zero_state(n, B)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    q8.adam8bit_step(w, dev(g), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **hp)
+    H.oracle_adam8(w_ref, g, st, B, hp=hp)
+    got = w.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), w_ref.view(np.uint32)), int((got.view(np.uint32) != w_ref.view(np.uint32)).sum())
+    H.assert_state_equal("states", d, st, w, w_ref)
