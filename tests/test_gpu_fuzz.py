@@ -1,0 +1,118 @@
+"""Seeded random sweep over sizes, block sizes, storage types, optimizers, flags and gradient
+scales (a fixed list of cases, so every run checks the same ones): stored weights, codes and
+absmax must equal the oracle's bit for bit after every step."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2412_01195_amd import synth
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+BLOCKS = (64, 128, 256, 512, 1024, 2048, 4096)
+TORCH_DT = {"f32": "float32", "bf16": "bfloat16", "f16": "float16"}
+
+
+@pytest.fixture(scope="module")
+def q8():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: the HIP path has no CPU fallback")
+    from paper_2412_01195_amd import q8opt
+    q8opt.lib()
+    return q8opt
+
+
+@pytest.fixture(scope="module")
+def tabs(q8):
+    return (q8.upload_qtable(q8.build_qtable(q8.build_codebook(True))),
+            q8.upload_qtable(q8.build_qtable(q8.build_codebook(False))))
+
+
+def to_store(x, store):
+    if store == "bf16":
+        return synth.bf16_bits(x)
+    if store == "f16":
+        return synth.f16_bits(x)
+    return np.ascontiguousarray(x, np.float32)
+
+
+def to_dev(a, store):
+    if store == "f32":
+        return torch.from_numpy(a.copy()).cuda()
+    return torch.from_numpy(a.view(np.int16).copy()).cuda().view(getattr(torch, TORCH_DT[store]))
+
+
+def from_dev(t, store):
+    if store == "f32":
+        return t.cpu().numpy().view(np.uint32)
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def make_grad(rng, n, scale):
+    g = rng.standard_normal(n) * scale
+    kind = rng.integers(0, 4)
+    if kind == 1:
+        g[rng.random(n) < 0.3] = 0.0                              # sparse gradient: exact zeros
+    elif kind == 2:
+        g = np.round(g / scale * 4) / 4 * scale                   # few distinct values: many equal quotients
+    elif kind == 3:
+        g *= 10.0 ** rng.uniform(-6, 0, n)                        # wide dynamic range inside blocks
+    return g.astype(np.float32)
+
+
+N_CASES = int(os.environ.get("Q8_FUZZ_CASES", "120"))      # a longer hunt: Q8_FUZZ_CASES=5000 pytest ...
+
+
+@pytest.mark.parametrize("case", range(N_CASES))
+def test_random_case(q8, tabs, case):
+    rng = np.random.default_rng(9000 + case)
+    n = int(rng.choice([rng.integers(1, 300), rng.integers(300, 6000), rng.integers(6000, 40000)]))
+    B = int(rng.choice(BLOCKS))
+    store = str(rng.choice(["f32", "bf16", "f16"]))
+    adam = bool(rng.integers(0, 2))
+    wd = float(rng.choice([0.0, 10.0 ** rng.uniform(-5, -1)]))
+    flags = int(rng.integers(0, 4)) if adam else 0
+    gmax = 3.0 if store == "f16" else 4.0                          # keep binary16 gradients finite
+    scale = 10.0 ** rng.uniform(-12, gmax)
+    steps = int(rng.integers(1, 5))
+    tag = "case %d: n=%d B=%d %s %s wd=%g flags=%d scale=%.2g" % (case, n, B, store, "adam" if adam else "sgd", wd, flags, scale)
+
+    w = to_store((rng.standard_normal(n) * 10.0 ** rng.uniform(-3, 0)).astype(np.float32), store)
+    st = H.zero_state(n, B, adam=adam)
+    w_d = to_dev(w, store)
+    st_d = {k: torch.from_numpy(v.copy()).cuda() for k, v in st.items()}
+    hp_a = dict(alpha=float(10.0 ** rng.uniform(-4, -2)), beta1=float(rng.choice([0.9, 0.8, 0.0])),
+                beta2=float(rng.choice([0.999, 0.99, 0.9])), eps=float(rng.choice([1e-8, 1e-6, 0.0 if scale > 1e-3 else 1e-8])))
+    hp_s = dict(alpha=float(10.0 ** rng.uniform(-3, -1)), beta=float(rng.choice([0.9, 0.5, 0.0])))
+    for t in range(1, steps + 1):
+        g32 = make_grad(rng, n, scale)
+        g = to_store(g32, store)
+        if adam and hp_a["eps"] == 0.0:                            # 0/0 is outside the method: no stored zero
+            stored_zero = (g32 == 0) if store == "f32" else ((g & 0x7fff) == 0)
+            g32[stored_zero] = np.float32(scale)
+            g = to_store(g32, store)
+        g_d = to_dev(g, store)
+        kw = dict(bf16=store == "bf16", f16=store == "f16")
+        if adam:
+            H.oracle_adam8(w, g, st, B, wd=wd, t=t, flags=flags, hp=hp_a, **kw)
+            fn = {"f32": q8.adam8bit_step, "bf16": q8.adam8bit_step_bf16, "f16": q8.adam8bit_step_f16}[store]
+            fn(w_d, g_d, st_d["m_q"], st_d["r_q"], st_d["N_m"], st_d["N_r"], tabs[0], tabs[1], B,
+               weight_decay=wd, t=t, flags=flags, **hp_a)
+        else:
+            H.oracle_sgd8(w, g, st, B, wd=wd, hp=hp_s, **kw)
+            fn = {"f32": q8.sgd8bit_step, "bf16": q8.sgd8bit_step_bf16, "f16": q8.sgd8bit_step_f16}[store]
+            fn(w_d, g_d, st_d["m_q"], st_d["N_m"], tabs[0], B, hp_s["alpha"], hp_s["beta"], weight_decay=wd)
+        got = from_dev(w_d, store)
+        ref = w.view(got.dtype)
+        same = (got == ref)
+        if store == "f32":
+            same |= (w_d.cpu().numpy() == 0) & (w == 0)            # the sign of an exact zero is not compared
+        assert same.all(), "%s step %d: %d weights differ" % (tag, t, int((~same).sum()))
+        for k, v in st.items():
+            a = st_d[k].cpu().numpy()
+            assert np.array_equal(a.view(np.uint8), v.view(np.uint8)), "%s step %d: %s differs" % (tag, t, k)
