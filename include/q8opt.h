@@ -198,7 +198,8 @@ Q8_API q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t* m_
  * above.  q8_plan_create copies the list into a device table it owns
  * (synchronous); the tensors themselves stay owned by the caller and must
  * outlive the plan's use.  r_q/N_r/r_f32 may be NULL for a plan that is only
- * used with the SGD entry point.  w and g of every tensor of a plan hold
+ * used with the SGD entry point.  A tensor with n == 0 is accepted and skipped
+ * (its pointers are not examined).  w and g of every tensor of a plan hold
  * binary32 (q8_plan_create), bfloat16 (q8_plan_create_bf16) or binary16
  * (q8_plan_create_f16), with the semantics of the 16-bit steps above; the
  * 32-bit states m_f32/r_f32 stay binary32.

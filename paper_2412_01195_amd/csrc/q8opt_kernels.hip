@@ -311,7 +311,9 @@ q8_status plan_create(const q8_tensor* list, int count, int B, Store store, q8_p
     bool has_r = true;
     for (int i = 0; i < count; ++i) {
         const q8_tensor& t = list[i];
-        if (t.n < 0 || !t.w || !t.g) return Q8_EINVAL;
+        if (t.n < 0) return Q8_EINVAL;
+        if (t.n == 0) continue;                       // an empty tensor contributes no unit; its pointers are not looked at
+        if (!t.w || !t.g) return Q8_EINVAL;
         if (!aligned(t.w, wg_al) || !aligned(t.g, wg_al)) return Q8_EALIGN;
         if (t.m_f32) {
             if (!aligned(t.m_f32, 16) || !aligned(t.r_f32, 16)) return Q8_EALIGN;

@@ -116,3 +116,92 @@ def test_random_case(q8, tabs, case):
         for k, v in st.items():
             a = st_d[k].cpu().numpy()
             assert np.array_equal(a.view(np.uint8), v.view(np.uint8)), "%s step %d: %s differs" % (tag, t, k)
+
+
+N_LISTS = int(os.environ.get("Q8_FUZZ_LISTS", "40"))
+
+
+@pytest.mark.parametrize("case", range(N_LISTS))
+def test_random_list(q8, tabs, case):
+    """Multi-tensor plans over random lists: empty, tiny and ragged tensors, 8-bit or 32-bit states
+    per tensor, any storage type, Adam or SGD; one launch per step, compared tensor by tensor."""
+    rng = np.random.default_rng(70000 + case)
+    B = int(rng.choice(BLOCKS))
+    store = str(rng.choice(["f32", "bf16", "f16"]))
+    adam = bool(rng.integers(0, 2))
+    wd = float(rng.choice([0.0, 10.0 ** rng.uniform(-4, -1)]))
+    flags = int(rng.integers(0, 4)) if adam else 0
+    hp_a = dict(alpha=float(10.0 ** rng.uniform(-4, -2)), beta1=0.9, beta2=float(rng.choice([0.999, 0.99])), eps=1e-8)
+    hp_s = dict(alpha=float(10.0 ** rng.uniform(-3, -1)), beta=0.9)
+    count = int(rng.integers(1, 14))
+    sizes = [int(rng.choice([0, rng.integers(1, 50), rng.integers(50, 3000), rng.integers(3000, 20000)])) for _ in range(count)]
+    if sum(sizes) == 0:
+        sizes[0] = 77
+    kw = dict(bf16=store == "bf16", f16=store == "f16")
+    tdt = getattr(torch, TORCH_DT[store])
+    tens, refs = [], []
+    for n in sizes:
+        small = bool(rng.integers(0, 2)) and n > 0
+        w = to_store((rng.standard_normal(n) * 0.1).astype(np.float32), store)
+        ref = dict(w=w, n=n, small=small, scale=10.0 ** rng.uniform(-8, 1))
+        d = dict(w=to_dev(w, store) if n else torch.empty(0, dtype=tdt, device="cuda"),
+                 g=torch.zeros(n, dtype=tdt, device="cuda"))
+        if small:
+            ref["m"] = np.zeros(n, np.float32); ref["r"] = np.zeros(n, np.float32)
+            d["m_f32"] = torch.zeros(n, device="cuda")
+            if adam:
+                d["r_f32"] = torch.zeros(n, device="cuda")
+        else:
+            ref["st"] = H.zero_state(n, B, adam=adam)
+            d.update({k: torch.from_numpy(v.copy()).cuda() for k, v in ref["st"].items()})
+        tens.append(d); refs.append(ref)
+    plan = q8.Plan(tens, B, wg_dtype=TORCH_DT[store])
+    widen = {"f32": lambda a: a, "bf16": lambda a: (a.astype(np.uint32) << 16).view(np.float32),
+             "f16": lambda a: a.view(np.float16).astype(np.float32)}[store]
+    narrow = {"bf16": oracle.f32_to_bf16, "f16": oracle.f32_to_f16}.get(store)
+    try:
+        for t in range(1, 4):
+            for d, ref in zip(tens, refs):
+                n = ref["n"]
+                if n == 0:
+                    continue
+                g = to_store(make_grad(rng, n, ref["scale"]), store)
+                d["g"].copy_(to_dev(g, store))
+                if ref["small"]:
+                    w32, g32 = widen(ref["w"]), widen(g)
+                    if store != "f32":
+                        w32 = w32.copy()
+                    if adam:
+                        oracle.adam32_step(w32, g32, ref["m"], ref["r"], hp_a["alpha"], hp_a["beta1"], hp_a["beta2"],
+                                           hp_a["eps"], wd, t, flags)
+                    else:
+                        oracle.sgd32_step(w32, g32, ref["m"], hp_s["alpha"], hp_s["beta"], wd)
+                    if store != "f32":
+                        ref["w"][:] = np.array([narrow(v) for v in w32], np.uint16)
+                elif adam:
+                    H.oracle_adam8(ref["w"], g, ref["st"], B, wd=wd, t=t, flags=flags, hp=hp_a, **kw)
+                else:
+                    H.oracle_sgd8(ref["w"], g, ref["st"], B, wd=wd, hp=hp_s, **kw)
+            if adam:
+                plan.multi_adam8bit_step(tabs[0], tabs[1], weight_decay=wd, t=t, flags=flags, **hp_a)
+            else:
+                plan.multi_sgd8bit_step(tabs[0], hp_s["alpha"], hp_s["beta"], weight_decay=wd)
+            for i, (d, ref) in enumerate(zip(tens, refs)):
+                if ref["n"] == 0:
+                    continue
+                tag = "list %d tensor %d (n=%d, %s, B=%d) step %d" % (case, i, ref["n"], store, B, t)
+                got = from_dev(d["w"], store)
+                want = ref["w"].view(got.dtype)
+                same = got == want
+                if store == "f32":
+                    same |= (d["w"].cpu().numpy() == 0) & (ref["w"] == 0)
+                assert same.all(), tag
+                if ref["small"]:
+                    assert np.array_equal(d["m_f32"].cpu().numpy().view(np.uint32), ref["m"].view(np.uint32)), tag
+                    if adam:
+                        assert np.array_equal(d["r_f32"].cpu().numpy().view(np.uint32), ref["r"].view(np.uint32)), tag
+                else:
+                    for k, v in ref["st"].items():
+                        assert np.array_equal(d[k].cpu().numpy().view(np.uint8), v.view(np.uint8)), (tag, k)
+    finally:
+        plan.destroy()
