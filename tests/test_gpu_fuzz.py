@@ -205,3 +205,56 @@ def test_random_list(q8, tabs, case):
                         assert np.array_equal(d[k].cpu().numpy().view(np.uint8), v.view(np.uint8)), (tag, k)
     finally:
         plan.destroy()
+
+
+@pytest.mark.parametrize("kind", ["linear", "cubic", "jittered-tree"])
+def test_other_codebooks(q8, kind):
+    """The kernels search whatever strictly increasing codebook the table was built from (nothing
+    about the dynamic-tree values is compiled in): quantize, dequantize and an Adam step with
+    other signed / unsigned maps equal the oracle run with the same maps."""
+    rng = np.random.default_rng(5)
+    j = np.arange(256, dtype=np.float64)
+    if kind == "linear":
+        qs = ((j - 127.0) / 128.0); qs[255] = 1.0
+        qu = j / 255.0
+    elif kind == "cubic":
+        x = (j - 127.0) / 128.0; x[255] = 1.0
+        qs = np.sign(x) * np.abs(x) ** 3
+        qu = (j / 255.0) ** 3
+    else:
+        qs0, qu0 = H.codebooks()
+        def jitter(q):
+            q = q.astype(np.float64).copy()
+            gap = np.diff(q)
+            step = rng.uniform(-0.2, 0.2, 254) * np.minimum(gap[:-1], gap[1:])
+            step[q[1:-1] == 0] = 0.0                     # the map keeps its exact 0.0
+            q[1:-1] += step
+            return q
+        qs, qu = jitter(qs0), jitter(qu0)
+    qs, qu = qs.astype(np.float32), qu.astype(np.float32)
+    assert np.all(np.diff(qs) > 0) and np.all(np.diff(qu) > 0)
+    ts = q8.upload_qtable(q8.build_qtable(qs)); tu = q8.upload_qtable(q8.build_qtable(qu))
+    n, B = 50000 + 37, 256
+    T = (rng.standard_normal(n) * 10.0 ** rng.uniform(-4, 1, n)).astype(np.float32)
+    for q, tab, x in ((qs, ts, T), (qu, tu, np.abs(T))):
+        TQ_ref, N_ref = oracle.quantize_blockwise(q, x, B)
+        TQ = torch.empty(n, dtype=torch.uint8, device="cuda"); N = torch.empty(oracle.nblocks(n, B), device="cuda")
+        q8.quantize_blockwise(tab, torch.from_numpy(x).cuda(), B, TQ, N)
+        assert np.array_equal(TQ.cpu().numpy(), TQ_ref) and np.array_equal(N.cpu().numpy().view(np.uint32), N_ref.view(np.uint32))
+        TD = torch.empty(n, device="cuda")
+        q8.dequantize_blockwise(tab, TQ, N, B, TD)
+        assert np.array_equal(TD.cpu().numpy().view(np.uint32), oracle.dequantize_blockwise(q, TQ_ref, N_ref, B).view(np.uint32))
+    # Adam with these maps: zero codes are those of 0.0 in each map
+    zs, zu = int(np.flatnonzero(qs == 0)[0]), int(np.flatnonzero(qu == 0)[0])
+    w = (rng.standard_normal(n) * 0.05).astype(np.float32)
+    st = dict(m_q=np.full(n, zs, np.uint8), r_q=np.full(n, zu, np.uint8),
+              N_m=np.zeros(oracle.nblocks(n, B), np.float32), N_r=np.zeros(oracle.nblocks(n, B), np.float32))
+    w_d = torch.from_numpy(w.copy()).cuda(); st_d = {k: torch.from_numpy(v.copy()).cuda() for k, v in st.items()}
+    for t in range(1, 4):
+        g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+        oracle.adam8bit_step(w, g, st["m_q"], st["r_q"], st["N_m"], st["N_r"], qs, qu, B, wd=1e-3, t=t, **H.ADAM)
+        q8.adam8bit_step(w_d, torch.from_numpy(g).cuda(), st_d["m_q"], st_d["r_q"], st_d["N_m"], st_d["N_r"], ts, tu, B,
+                         weight_decay=1e-3, t=t, **H.ADAM)
+        assert np.array_equal(w_d.cpu().numpy().view(np.uint32), w.view(np.uint32)), (kind, t)
+        for k, v in st.items():
+            assert np.array_equal(st_d[k].cpu().numpy().view(np.uint8), v.view(np.uint8)), (kind, t, k)
