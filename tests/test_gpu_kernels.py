@@ -369,3 +369,45 @@ def test_weight_update_quotient_bits(q8, tabs, eps):
     got = w.cpu().numpy()
     assert np.array_equal(got.view(np.uint32), w_ref.view(np.uint32)), int((got.view(np.uint32) != w_ref.view(np.uint32)).sum())
     H.assert_state_equal("states", d, st, w, w_ref)
+
+
+def test_host_threads_launch_concurrently(q8, tabs):
+    """Four host threads, each with its own stream and tensor, call the library at the same time
+    (ctypes releases the GIL during the call): the per-device records and occupancy caches are
+    shared, the results must not be."""
+    import threading
+    n, B, steps, nthr = (1 << 18) + 333, 1024, 25, 4
+    hosts, devs, grads = [], [], []
+    for k in range(nthr):
+        w_ref = synth.uniform_weights(900 + k, 0, n)
+        st = H.zero_state(n, B)
+        hosts.append((w_ref, st))
+        devs.append((dev(w_ref), {kk: dev(v) for kk, v in st.items()}))
+        grads.append([dev(synth.normal_grad(900 + k, 0, t, n, 1e-3)) for t in range(1, 4)])
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(k):
+        try:
+            s = torch.cuda.Stream()
+            w, d = devs[k]
+            with torch.cuda.stream(s):
+                for t in range(1, steps + 1):
+                    q8.adam8bit_step(w, grads[k][t % 3], d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B,
+                                     **H.ADAM, t=t)
+            s.synchronize()
+        except Exception as e:                      # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(nthr)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for k in range(nthr):
+        w_ref, st = hosts[k]
+        for t in range(1, steps + 1):
+            H.oracle_adam8(w_ref, grads[k][t % 3].cpu().numpy(), st, B, t=t)
+        H.assert_state_equal("thread %d" % k, devs[k][1], st, devs[k][0], w_ref)
