@@ -139,6 +139,14 @@ def build_workload(name, torch, q8opt, dev):
         def step():
             q8opt.sgd8bit_step(w, g, st["m_q"], st["N_m"], tab_s, B, 0.1, 0.9, 1e-4)
         return wl["name"], n, 14 * n + 8 * (-(-n // B)), "sgd8_kernel<%d, float>" % B, step, None, keep
+    if name == "probe1b":
+        n = 1_000_000_000
+        w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
+        g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen)
+        st = state8(n, 2048, True)
+        return ("traffic of the config-4 step without its arithmetic (measurement aid): read w, g, both code arrays, "
+                "write w and both code arrays back unchanged; 1e9 params", n, 16 * n, "traffic_probe_kernel",
+                lambda: q8opt.probe_adam8bit_traffic(w, g, st["m_q"], st["r_q"], tab_s, tab_u), None, keep)
     if name in ("quant1b", "dequant1b"):
         n, B = 1_000_000_000, 2048
         nb = -(-n // B)
@@ -216,7 +224,7 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="1b",
-                    choices=["1b", "1m", "1b256", "100m", "bf16_1b", "f16_1b", "sgd1b", "quant1b", "dequant1b", "c2", "c3", "c5", "df"],
+                    choices=["1b", "1m", "1b256", "100m", "bf16_1b", "f16_1b", "sgd1b", "probe1b", "quant1b", "dequant1b", "c2", "c3", "c5", "df"],
                     help="1b (default) = configuration 4, the one the headline metric is quoted on")
     ap.add_argument("--block-size", type=int, default=0,
                     help="override the block size B of a flat workload (block-size sweep; not the headline line)")

@@ -230,6 +230,17 @@ Q8_API q8_status q8_multi_adam8bit_step(q8_plan* plan,
 Q8_API q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_signed,
                                 float alpha, float beta, float weight_decay, void* stream);
 
+/*
+ * Measurement aid, not part of the method: moves exactly the bytes of one
+ * q8_adam8bit_step at B = 2048 (reads w, g, m_q, r_q; writes w, m_q, r_q) with the
+ * same tiles, scheduler, LDS footprint and occupancy, but no arithmetic -- every
+ * value is written back unchanged.  Its rate is the ceiling of the step's access
+ * pattern on the chip; bench.py --workload probe1b reports it.
+ */
+Q8_API q8_status q8_probe_adam8bit_traffic(float* w, const float* g, uint8_t* m_q, uint8_t* r_q,
+                                    const void* qtable_signed, const void* qtable_unsigned,
+                                    int64_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

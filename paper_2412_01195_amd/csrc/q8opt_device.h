@@ -1130,6 +1130,70 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2)
     leave(sched);
 }
 
+#ifdef Q8_WITH_TRAFFIC_PROBE      // compiled into the host translation unit only
+// Measurement aid: the memory traffic of one Adam (8-bit) step at B = 2048 -- same wave
+// tiles, same scheduler, same LDS footprint and occupancy, same one barrier per job --
+// with the arithmetic left out: w and both code arrays are written back unchanged, g is
+// only read.  Its rate is what this access pattern can reach on the chip.
+__global__ __launch_bounds__(kWgThreads, Q8_MIN_WAVES) void traffic_probe_kernel(StepArgs a)
+{
+    using S = Shape<2048>;
+    __shared__ __attribute__((aligned(16))) Lds lds;
+    first_draw<kStepSpan>(a.sched, &lds.box);
+    stage_first(lds.tab, a.qtab_s, threadIdx.x);
+    stage_second(lds.tab, a.qtab_u, threadIdx.x);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int part = wave % S::WPB;
+    const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
+    const int64_t n = a.single.n;
+    gfloat* w = (gfloat*)a.single.w;
+    gcfloat* g = (gcfloat*)a.single.g;
+    gbyte* m_q = (gbyte*)a.single.m_q;
+    gbyte* r_q = (gbyte*)a.single.r_q;
+    const bool once = single_draw<kStepSpan>(njobs);
+    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
+        if (once && !first) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds.box, parity, njobs, first);
+        if (j0 >= njobs) break;
+        const int64_t u = j0 * S::UPJ + wave / S::WPB;
+        const int64_t base = u * S::UNIT + (int64_t)part * kWaveElems;
+        float wv[kWaveRows][4], gv[kWaveRows][4];
+        uint32_t mq[kWaveRows], rq[kWaveRows];
+        int cnt[kWaveRows];
+#pragma unroll
+        for (int r = 0; r < kWaveRows; ++r) {
+            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+            cnt[r] = (u < a.nunits) ? lane_count(n, e0) : 0;
+            if (cnt[r] > 0) {
+                load4f(w + e0, cnt[r], wv[r]);
+                load4f(g + e0, cnt[r], gv[r]);
+                mq[r] = load4b(m_q + e0, cnt[r]);
+                rq[r] = load4b(r_q + e0, cnt[r]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(gv[r][j]));      // keep the loads of g
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kWaveRows; ++r) {
+            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+            if (cnt[r] > 0) store4f(w + e0, cnt[r], wv[r]);
+        }
+        __syncthreads();                               // stands for the exchange of block maxima
+#pragma unroll
+        for (int r = 0; r < kWaveRows; ++r) {
+            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+            if (cnt[r] > 0) {
+                store4b(m_q + e0, cnt[r], mq[r]);
+                store4b(r_q + e0, cnt[r], rq[r]);
+            }
+        }
+    }
+    leave(a.sched);
+}
+#endif
+
 // ---------------------------------------------------------------------------
 // Launch helpers (host).
 // ---------------------------------------------------------------------------
@@ -1209,6 +1273,19 @@ q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* 
     hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, nunits, slot);
     return launch_status();
 }
+
+#ifdef Q8_WITH_TRAFFIC_PROBE
+inline q8_status launch_traffic_probe(StepArgs a, hipStream_t stream)
+{
+    static std::atomic<int> per_cu{0};
+    int grid;
+    q8_status st = grid_for(traffic_probe_kernel, per_cu, (a.nunits + Shape<2048>::UPJ - 1) / Shape<2048>::UPJ, grid,
+                            &a.sched);
+    if (st != Q8_OK) return st;
+    hipLaunchKernelGGL(traffic_probe_kernel, dim3(grid), dim3(kWgThreads), 0, stream, a);
+    return launch_status();
+}
+#endif
 
 }  // namespace
 }  // namespace q8

@@ -2,6 +2,7 @@
 // the kernels that do not depend on the storage type of w and g (stand-alone quantize and
 // dequantize).  The optimizer-step kernels are instantiated in q8opt_steps.hip, once per
 // storage type.
+#define Q8_WITH_TRAFFIC_PROBE
 #include "q8opt_device.h"
 
 #include <math.h>
@@ -295,6 +296,24 @@ extern "C" q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t
         int64_t n, int B, float alpha, float beta, float weight_decay, void* stream)
 {
     return sgd_step(kStoreF16, w, g, m_q, N_m, qtable_signed, n, B, alpha, beta, weight_decay, stream);
+}
+
+extern "C" q8_status q8_probe_adam8bit_traffic(float* w, const float* g, uint8_t* m_q, uint8_t* r_q,
+                                               const void* qtable_signed, const void* qtable_unsigned, int64_t n,
+                                               void* stream)
+{
+    if (n < 0) return Q8_EINVAL;
+    if (n == 0) return Q8_OK;
+    if (!w || !g || !m_q || !r_q || !qtable_signed || !qtable_unsigned) return Q8_EINVAL;
+    if (!aligned(w, 16) || !aligned(g, 16) || !aligned(m_q, 4) || !aligned(r_q, 4) || !aligned(qtable_signed, 16) ||
+        !aligned(qtable_unsigned, 16))
+        return Q8_EALIGN;
+    StepArgs a{};
+    a.single = TensorDesc{w, g, m_q, r_q, nullptr, nullptr, nullptr, nullptr, n};
+    a.nunits = (n + 2047) / 2048;
+    a.qtab_s = qtable_signed;
+    a.qtab_u = qtable_unsigned;
+    return launch_traffic_probe(a, static_cast<hipStream_t>(stream));
 }
 
 namespace {

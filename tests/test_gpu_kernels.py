@@ -411,3 +411,16 @@ def test_host_threads_launch_concurrently(q8, tabs):
         for t in range(1, steps + 1):
             H.oracle_adam8(w_ref, grads[k][t % 3].cpu().numpy(), st, B, t=t)
         H.assert_state_equal("thread %d" % k, devs[k][1], st, devs[k][0], w_ref)
+
+
+def test_traffic_probe_leaves_everything_unchanged(q8, tabs):
+    """The measurement aid rewrites w and both code arrays with the values it read."""
+    n = 2048 * 9 + 777
+    rng = np.random.default_rng(3)
+    w0 = rng.standard_normal(n).astype(np.float32); g0 = rng.standard_normal(n).astype(np.float32)
+    m0 = rng.integers(0, 256, n, dtype=np.uint8); r0 = rng.integers(0, 256, n, dtype=np.uint8)
+    w, g, m, r = dev(w0), dev(g0), dev(m0), dev(r0)
+    q8.probe_adam8bit_traffic(w, g, m, r, tabs[0], tabs[1])
+    q8.probe_adam8bit_traffic(w, g, m, r, tabs[0], tabs[1])
+    assert np.array_equal(w.cpu().numpy().view(np.uint32), w0.view(np.uint32)) and np.array_equal(g.cpu().numpy(), g0)
+    assert np.array_equal(m.cpu().numpy(), m0) and np.array_equal(r.cpu().numpy(), r0)
