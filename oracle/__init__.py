@@ -18,36 +18,41 @@ FLAG_DECOUPLED_WD = 2
 _lib = None
 
 
+def bind(L):
+    """Declare the argument types of the oracle's functions on a loaded library."""
+    fp, u8p, i64, i32, f32 = C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_float
+    L.oracle_build_codebook.argtypes = [i32, fp]
+    L.oracle_nearest_code.argtypes = [fp, f32]
+    L.oracle_nearest_code_bruteforce.argtypes = [fp, f32]
+    L.oracle_quantize_blockwise.argtypes = [fp, fp, i64, i32, u8p, fp]
+    L.oracle_dequantize_blockwise.argtypes = [fp, u8p, fp, i64, i32, fp]
+    L.oracle_adam32_step.argtypes = [fp, fp, fp, fp, i64, f32, f32, f32, f32, f32, i64, i32]
+    L.oracle_sgd32_step.argtypes = [fp, fp, fp, i64, f32, f32, f32]
+    L.oracle_adam_scalars.argtypes = [f32, f32, f32, f32, f32, i64, i32, fp]
+    L.oracle_adam8bit_step.argtypes = [fp, fp, u8p, u8p, fp, fp, fp, fp, i64, i32,
+                                       f32, f32, f32, f32, f32, i64, i32]
+    L.oracle_sgd8bit_step.argtypes = [fp, fp, u8p, fp, fp, i64, i32, f32, f32, f32]
+    L.oracle_adam8bit_step_bf16.argtypes = L.oracle_adam8bit_step.argtypes
+    L.oracle_sgd8bit_step_bf16.argtypes = L.oracle_sgd8bit_step.argtypes
+    L.oracle_adam8bit_step_f16.argtypes = L.oracle_adam8bit_step.argtypes
+    L.oracle_sgd8bit_step_f16.argtypes = L.oracle_sgd8bit_step.argtypes
+    L.oracle_f16_to_f32.argtypes = [C.c_uint16]; L.oracle_f16_to_f32.restype = f32
+    L.oracle_f32_to_f16.argtypes = [f32]; L.oracle_f32_to_f16.restype = C.c_uint16
+    L.oracle_bf16_to_f32.argtypes = [C.c_uint16]; L.oracle_bf16_to_f32.restype = f32
+    L.oracle_f32_to_bf16.argtypes = [f32]; L.oracle_f32_to_bf16.restype = C.c_uint16
+    for name in ("oracle_build_codebook", "oracle_nearest_code", "oracle_nearest_code_bruteforce",
+                 "oracle_quantize_blockwise", "oracle_dequantize_blockwise", "oracle_adam32_step",
+                 "oracle_sgd32_step", "oracle_adam_scalars", "oracle_adam8bit_step", "oracle_sgd8bit_step",
+                 "oracle_adam8bit_step_bf16", "oracle_sgd8bit_step_bf16",
+                 "oracle_adam8bit_step_f16", "oracle_sgd8bit_step_f16"):
+        getattr(L, name).restype = i32
+    return L
+
+
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(_build())
-        fp, u8p, i64, i32, f32 = C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_float
-        L.oracle_build_codebook.argtypes = [i32, fp]
-        L.oracle_nearest_code.argtypes = [fp, f32]
-        L.oracle_nearest_code_bruteforce.argtypes = [fp, f32]
-        L.oracle_quantize_blockwise.argtypes = [fp, fp, i64, i32, u8p, fp]
-        L.oracle_dequantize_blockwise.argtypes = [fp, u8p, fp, i64, i32, fp]
-        L.oracle_adam32_step.argtypes = [fp, fp, fp, fp, i64, f32, f32, f32, f32, f32, i64, i32]
-        L.oracle_sgd32_step.argtypes = [fp, fp, fp, i64, f32, f32, f32]
-        L.oracle_adam8bit_step.argtypes = [fp, fp, u8p, u8p, fp, fp, fp, fp, i64, i32,
-                                           f32, f32, f32, f32, f32, i64, i32]
-        L.oracle_sgd8bit_step.argtypes = [fp, fp, u8p, fp, fp, i64, i32, f32, f32, f32]
-        L.oracle_adam8bit_step_bf16.argtypes = L.oracle_adam8bit_step.argtypes
-        L.oracle_sgd8bit_step_bf16.argtypes = L.oracle_sgd8bit_step.argtypes
-        L.oracle_adam8bit_step_f16.argtypes = L.oracle_adam8bit_step.argtypes
-        L.oracle_sgd8bit_step_f16.argtypes = L.oracle_sgd8bit_step.argtypes
-        L.oracle_f16_to_f32.argtypes = [C.c_uint16]; L.oracle_f16_to_f32.restype = f32
-        L.oracle_f32_to_f16.argtypes = [f32]; L.oracle_f32_to_f16.restype = C.c_uint16
-        L.oracle_bf16_to_f32.argtypes = [C.c_uint16]; L.oracle_bf16_to_f32.restype = f32
-        L.oracle_f32_to_bf16.argtypes = [f32]; L.oracle_f32_to_bf16.restype = C.c_uint16
-        for name in ("oracle_build_codebook", "oracle_nearest_code", "oracle_nearest_code_bruteforce",
-                     "oracle_quantize_blockwise", "oracle_dequantize_blockwise", "oracle_adam32_step",
-                     "oracle_sgd32_step", "oracle_adam8bit_step", "oracle_sgd8bit_step",
-                     "oracle_adam8bit_step_bf16", "oracle_sgd8bit_step_bf16",
-                     "oracle_adam8bit_step_f16", "oracle_sgd8bit_step_f16"):
-            getattr(L, name).restype = i32
-        _lib = L
+        _lib = bind(C.CDLL(_build()))
     return _lib
 
 
@@ -103,6 +108,13 @@ def adam32_step(w, g, m, r, alpha, beta1, beta2, eps, wd=0.0, t=1, flags=0):
     assert g.size == n and m.size == n and r.size == n
     _ok(lib().oracle_adam32_step(_p(w, np.float32), _p(g, np.float32), _p(m, np.float32), _p(r, np.float32),
                                  n, alpha, beta1, beta2, eps, wd, t, flags))
+
+
+def adam_scalars(alpha, beta1, beta2, eps, wd=0.0, t=1, flags=0) -> dict:
+    """The binary32 scalars the Adam step derives from its hyper-parameters."""
+    out = np.empty(5, np.float32)
+    _ok(lib().oracle_adam_scalars(alpha, beta1, beta2, eps, wd, t, flags, _p(out, np.float32)))
+    return dict(omb1=out[0], omb2=out[1], alpha_t=out[2], isbc2=out[3], alpha_wd=out[4])
 
 
 def sgd32_step(w, g, m, alpha, beta, wd=0.0):

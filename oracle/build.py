@@ -1,10 +1,13 @@
-"""Compile the CPU oracle (test infrastructure) into oracle/libq8_oracle.so."""
+"""Compile the CPU oracle (test infrastructure) into oracle/libq8_oracle.so.
+
+Q8_ORACLE_SRC names another C source to compile instead (the mutation tests build altered
+copies of the oracle this way, next to that source); nothing else reads it."""
 import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "q8_oracle.c")
-LIB = os.path.join(HERE, "libq8_oracle.so")
+SRC = os.environ.get("Q8_ORACLE_SRC") or os.path.join(HERE, "q8_oracle.c")
+LIB = (os.path.splitext(SRC)[0] + ".so") if os.environ.get("Q8_ORACLE_SRC") else os.path.join(HERE, "libq8_oracle.so")
 CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra"]
 
 

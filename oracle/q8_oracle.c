@@ -17,8 +17,11 @@
  * Pins (tests/test_oracle_*.py): codebook structure against an independent
  * rational-arithmetic bit-field decoder; nearest-code search against a 256-way
  * exact argmin; round-trip error bound; fp32-state updates against closed forms
- * and against an independently written recurrence.  Every function here has at
- * least one such pin.
+ * and against an independently written recurrence, bit for bit, with and without
+ * the two extension flags; the bias-correction scalars against exact rational
+ * arithmetic.  Every function here has at least one such pin, and
+ * tests/test_oracle_mutations.py plants single mistakes in a copy of this file
+ * and checks that the pins catch each of them.
  */
 #include <math.h>
 #include <stddef.h>
@@ -176,22 +179,19 @@ int oracle_dequantize_blockwise(const float *q, const uint8_t *TQ, const float *
 }
 
 /* ------------------------------------------------------------------------- */
-/* Scalars derived from the hyper-parameters.                                 */
+/* Scalars derived from the hyper-parameters.  1 - beta1 and 1 - beta2 are    */
+/* binary32 subtractions (Eq. adam as printed needs nothing else).            */
+/*                                                                           */
+/* Extensions outside Eq. adam (the paper trains its DF-ResNets with AdamW,   */
+/* weight decay 0.05, Sec. V "Training settings", but prints neither the      */
+/* decay nor a bias correction):                                              */
+/*   bias correction  : the step is alpha / (1 - beta1^t) and the root of r   */
+/*                      is multiplied by 1 / sqrt(1 - beta2^t); both scalars   */
+/*                      are evaluated in binary64 (beta^t by the C library's  */
+/*                      pow) and rounded once to binary32;                    */
+/*   decoupled decay  : w <- w - (alpha * wd) * w before the step, with       */
+/*                      alpha * wd one binary32 product.                      */
 /* ------------------------------------------------------------------------- */
-static double ipow(double base, int64_t e)     /* left-to-right binary power  */
-{
-    double r = 1.0;
-    int top = 62;
-    while (top > 0 && !((e >> top) & 1))
-        --top;
-    for (int b = top; b >= 0; --b) {
-        r = r * r;
-        if ((e >> b) & 1)
-            r = r * base;
-    }
-    return (e <= 0) ? 1.0 : r;
-}
-
 typedef struct {
     float alpha, beta1, beta2, eps, wd;
     float omb1, omb2;        /* 1 - beta1, 1 - beta2, binary32 subtraction     */
@@ -211,8 +211,8 @@ static adam_scalars adam_prepare(float alpha, float beta1, float beta2, float ep
     s.alpha_t = alpha;
     s.isbc2 = 1.0f;
     if (flags & ORACLE_FLAG_BIAS_CORRECTION) {
-        double bc1 = 1.0 - ipow((double)beta1, t);
-        double bc2 = 1.0 - ipow((double)beta2, t);
+        double bc1 = 1.0 - pow((double)beta1, (double)t);
+        double bc2 = 1.0 - pow((double)beta2, (double)t);
         s.alpha_t = (float)((double)alpha / bc1);
         s.isbc2 = (float)(1.0 / sqrt(bc2));
     }
@@ -220,10 +220,24 @@ static adam_scalars adam_prepare(float alpha, float beta1, float beta2, float ep
     return s;
 }
 
+/* The derived scalars, for the tests that pin them: out = {1-beta1, 1-beta2,  */
+/* alpha_t, isbc2, alpha*wd}.                                                 */
+int oracle_adam_scalars(float alpha, float beta1, float beta2, float eps, float wd,
+                        int64_t t, int flags, float *out5)
+{
+    adam_scalars s = adam_prepare(alpha, beta1, beta2, eps, wd, t, flags);
+    out5[0] = s.omb1; out5[1] = s.omb2; out5[2] = s.alpha_t; out5[3] = s.isbc2; out5[4] = s.alpha_wd;
+    return 0;
+}
+
 /* ------------------------------------------------------------------------- */
 /* One element of Eq. adam, from 32-bit previous states.  As printed in the   */
 /* paper there is no bias-correction term; (1-beta2) g^2 is ((1-beta2) g) g.  */
-/* Coupled decay (g + wd*w) is applied only when wd != 0.                     */
+/* Coupled decay (g + wd*w) is applied only when wd != 0.  Every statement is */
+/* one rounded binary32 operation, also in the two extensions: with bias      */
+/* correction the root is first scaled (one product), then eps is added;      */
+/* decoupled decay shrinks w (one product, one difference) before the step    */
+/* is subtracted.                                                             */
 /* ------------------------------------------------------------------------- */
 static void adam_element(const adam_scalars *s, float *w, float g,
                          float m_prev, float r_prev, float *m_new, float *r_new)
@@ -243,7 +257,8 @@ static void adam_element(const adam_scalars *s, float *w, float g,
     float root = sqrtf(r);
     float d, u, t6;
     if (s->flags & ORACLE_FLAG_BIAS_CORRECTION) {
-        d = fmaf(root, s->isbc2, s->eps);      /* one fused operation, by definition of this extension */
+        float rs = root * s->isbc2;
+        d = rs + s->eps;
         u = m / d;
         t6 = s->alpha_t * u;
     } else {

@@ -106,9 +106,136 @@ def test_sgd32_equals_numpy_and_closed_form():
     assert np.array_equal(m, g) and np.array_equal(w, 1 - 0.5 * g)      # m_0 = g_0
 
 
-def test_bias_correction_and_decoupled_decay_extension():
-    """Extension flags (not printed in Eq. adam): w -= alpha/(1-b1^t) * m / (sqrt(r)/sqrt(1-b2^t) + eps),
-    and w <- w - alpha*wd*w before the step."""
+# ------------------------------------------------------------------ extension flags
+# Bias correction and decoupled decay are not printed in Eq. adam (the paper only names AdamW
+# with weight decay 0.05 in its training settings), so their definition is this build's own:
+#   alpha_t = RN32( alpha / (1 - beta1^t) ),  c = RN32( 1 / sqrt(1 - beta2^t) )   [binary64 inside]
+#   d = RN(RN(sqrt(r) * c) + eps);  w' = RN(w - RN(RN(alpha*wd) * w));  w = RN(w' - RN(alpha_t * RN(m/d)))
+# The pins below hold the C code to that definition bit for bit.
+def np_scalars(alpha, beta1, beta2, t):
+    """alpha_t and c formed in binary64 from the binary32 hyper-parameters, rounded once."""
+    a, b1, b2 = (np.float64(f32(x)) for x in (alpha, beta1, beta2))
+    bc1 = np.float64(1.0) - b1 ** np.float64(t)
+    bc2 = np.float64(1.0) - b2 ** np.float64(t)
+    return f32(a / bc1), f32(np.float64(1.0) / np.sqrt(bc2))
+
+
+def np_adam_ext(w, g, m, r, alpha, beta1, beta2, eps, wd, t, flags):
+    """One step with the extension flags, one binary32 operation per numpy call."""
+    a, b1, b2, e, lam = f32(alpha), f32(beta1), f32(beta2), f32(eps), f32(wd)
+    bias, decoupled = bool(flags & oracle.FLAG_BIAS_CORRECTION), bool(flags & oracle.FLAG_DECOUPLED_WD)
+    if wd and not decoupled:
+        g = g + lam * w
+    m = b1 * m + (f32(1) - b1) * g
+    r = b2 * r + ((f32(1) - b2) * g) * g
+    root = np.sqrt(r)
+    if bias:
+        a_t, c = np_scalars(alpha, beta1, beta2, t)
+        step = a_t * (m / (root * c + e))
+    else:
+        step = a * (m / (root + e))
+    if wd and decoupled:
+        w = w - (a * lam) * w
+    return w - step, m, r
+
+
+@pytest.mark.parametrize("flags", [1, 2, 3])
+@pytest.mark.parametrize("t0", [1, 997])
+def test_extension_flags_equal_numpy_recurrence_bitwise(flags, t0):
+    rng = np.random.default_rng(40 + flags)
+    n = 6000
+    w = rng.uniform(-0.1, 0.1, n).astype(f32); m = np.zeros(n, f32); r = np.zeros(n, f32)
+    w2, m2, r2 = w.copy(), m.copy(), r.copy()
+    for t in range(t0, t0 + 6):
+        g = (rng.standard_normal(n) * 1e-3).astype(f32)
+        oracle.adam32_step(w, g, m, r, **ADAM, wd=0.05, t=t, flags=flags)
+        w2, m2, r2 = np_adam_ext(w2, g, m2, r2, **ADAM, wd=0.05, t=t, flags=flags)
+        assert w2.dtype == f32
+        assert np.array_equal(m, m2) and np.array_equal(r, r2)
+        assert np.array_equal(w, w2), "flags %d step %d: %d weights differ" % (flags, t, (w != w2).sum())
+
+
+def test_extension_pin_tells_the_plausible_variants_apart():
+    """The inputs of the bit-for-bit pin above separate the definition from its nearest
+    variants: a fused sqrt(r)*c + eps, step before decay, and binary32 scalars."""
+    rng = np.random.default_rng(43)
+    n = 6000
+    w = rng.uniform(-0.1, 0.1, n).astype(f32)
+    g = (rng.standard_normal(n) * 1e-3).astype(f32)
+    m = (rng.standard_normal(n) * 1e-3).astype(f32); r = (rng.random(n) * 1e-6).astype(f32)
+    t = 7
+    ref, _, _ = np_adam_ext(w, g, m, r, **ADAM, wd=0.05, t=t, flags=3)
+    a_t, c = np_scalars(ADAM["alpha"], ADAM["beta1"], ADAM["beta2"], t)
+    _, m1, r1 = np_adam_ext(w, g, m, r, **ADAM, wd=0.0, t=t, flags=0)
+    root = np.sqrt(r1)
+    fused = (root.astype(np.float64) * np.float64(c) + np.float64(f32(1e-8))).astype(f32)    # exact product, one rounding
+    w_fused = (w - (f32(1e-3) * f32(0.05)) * w) - a_t * (m1 / fused)
+    assert (w_fused != ref).sum() > 10
+    w_swapped = w - a_t * (m1 / (root * c + f32(1e-8)))
+    w_swapped = w_swapped - (f32(1e-3) * f32(0.05)) * w          # decay applied after the step, to the old w
+    assert (w_swapped != ref).sum() > 10
+    differs = 0
+    for tt in range(1, 40):
+        a64, c64 = np_scalars(1e-3, 0.9, 0.999, tt)
+        a32 = f32(1e-3) / (f32(1) - f32(0.9) ** f32(tt))
+        c32 = f32(1) / np.sqrt(f32(1) - f32(0.999) ** f32(tt))
+        differs += int(a32 != a64) + int(c32 != c64)
+    assert differs > 10
+
+
+def _fraction_of(x):
+    from fractions import Fraction
+    return Fraction(float(x))
+
+
+@pytest.mark.parametrize("t", [1, 2, 3, 7, 10, 100, 997, 1000, 4321, 10 ** 6, 10 ** 9])
+@pytest.mark.parametrize("betas", [(0.9, 0.999), (0.8, 0.99), (0.95, 0.9999)])
+def test_bias_correction_scalars_are_correctly_rounded(t, betas):
+    """alpha / (1 - beta1^t) and 1 / sqrt(1 - beta2^t) as real numbers, from the binary32
+    hyper-parameters, rounded to nearest binary32: checked in exact rational arithmetic
+    (the square root through the squares of the rounding interval's end points)."""
+    from fractions import Fraction
+    alpha = 1e-3
+    b1, b2 = betas
+    s = oracle.adam_scalars(alpha, b1, b2, 1e-8, wd=0.05, t=t, flags=oracle.FLAG_BIAS_CORRECTION)
+    assert s["omb1"] == f32(1) - f32(b1) and s["omb2"] == f32(1) - f32(b2)
+    assert s["alpha_wd"] == f32(alpha) * f32(0.05)
+
+    def power_enclosure(beta):
+        """[lo, hi] around beta^t: exact for moderate t; for huge t, 0 < beta^t <= exp(-t (1 - beta))
+        (ln x <= x - 1), which the assertion keeps below 1e-40."""
+        fb = _fraction_of(f32(beta))
+        if t <= 5000:
+            return fb ** t, fb ** t
+        assert t * (1.0 - float(f32(beta))) > 93.0          # exp(-93) < 1e-40
+        return Fraction(0), Fraction(1, 10 ** 40)
+    lo1, hi1 = power_enclosure(b1)
+    lo2, hi2 = power_enclosure(b2)
+
+    def half_ulp_interval(x):
+        x = f32(x)
+        dn, up = np.nextafter(x, f32(-np.inf)), np.nextafter(x, f32(np.inf))
+        return (_fraction_of(x) + _fraction_of(dn)) / 2, (_fraction_of(x) + _fraction_of(up)) / 2
+    # alpha_t: the exact quotient lies in the rounding interval of the stored value
+    lo, hi = half_ulp_interval(s["alpha_t"])
+    q_lo = _fraction_of(f32(alpha)) / (1 - lo1)
+    q_hi = _fraction_of(f32(alpha)) / (1 - hi1)
+    assert lo <= q_lo and q_hi <= hi
+    # isbc2: lo <= 1/sqrt(bc2) <= hi  <=>  lo^2 * bc2 <= 1 <= hi^2 * bc2
+    lo, hi = half_ulp_interval(s["isbc2"])
+    assert lo * lo * (1 - lo2) <= 1 and hi * hi * (1 - hi2) >= 1
+    assert lo * lo * (1 - hi2) <= 1 and hi * hi * (1 - lo2) >= 1
+
+
+def test_flags_zero_ignore_the_step_count():
+    s0 = oracle.adam_scalars(1e-3, 0.9, 0.999, 1e-8, t=1)
+    s9 = oracle.adam_scalars(1e-3, 0.9, 0.999, 1e-8, t=9)
+    assert s0 == s9 and s0["alpha_t"] == f32(1e-3) and s0["isbc2"] == f32(1)
+
+
+def test_bias_corrected_adamw_tracks_the_textbook_form():
+    """Loose sanity check against the textbook statement in binary64: m/(1-b1^t), r/(1-b2^t),
+    w <- w (1 - alpha wd) - alpha mhat / (sqrt(rhat) + eps)."""
     rng = np.random.default_rng(4)
     n = 2000
     w = rng.uniform(-0.1, 0.1, n).astype(f32); m = np.zeros(n, f32); r = np.zeros(n, f32)
