@@ -56,6 +56,29 @@ def measured_traffic(path: str):
         return None
 
 
+def load_traffic_probe():
+    """The benchmark's own measurement aid (workload probe1b): libq8opt_probe.so, built next to the
+    product library from the same objects plus csrc/q8opt_probe.hip.  Returns a function
+    probe(w, g, m_q, r_q, qtable_signed, qtable_unsigned) that moves the bytes of one Adam step at
+    B = 2048 without its arithmetic (all values written back unchanged)."""
+    import ctypes as C
+    import torch
+    from paper_2412_01195_amd import q8opt
+    path = os.path.join(os.path.dirname(q8opt.LIB_PATH), "libq8opt_probe.so")
+    if not os.path.exists(path):
+        raise ImportError("libq8opt_probe.so is not built (%s); run __graft_entry__.build()" % path)
+    L = C.CDLL(path)
+    L.q8_probe_adam8bit_traffic.argtypes = [C.c_void_p] * 6 + [C.c_int64, C.c_void_p]
+    L.q8_probe_adam8bit_traffic.restype = C.c_int
+
+    def probe(w, g, m_q, r_q, tab_s, tab_u):
+        st = L.q8_probe_adam8bit_traffic(w.data_ptr(), g.data_ptr(), m_q.data_ptr(), r_q.data_ptr(), tab_s.data_ptr(),
+                                         tab_u.data_ptr(), w.numel(), torch.cuda.current_stream().cuda_stream)
+        if st != 0:
+            raise RuntimeError("q8_probe_adam8bit_traffic failed with status %d" % st)
+    return probe
+
+
 def cpu_baseline(w_dev, g_dev, B: int, sample: int, steps: int):
     """The CPU oracle, as it stands, on the first `sample` parameters of the same workload,
     split at block boundaries over the host threads available to this process."""
@@ -144,9 +167,10 @@ def build_workload(name, torch, q8opt, dev):
         w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
         g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen)
         st = state8(n, 2048, True)
+        probe = load_traffic_probe()
         return ("traffic of the config-4 step without its arithmetic (measurement aid): read w, g, both code arrays, "
                 "write w and both code arrays back unchanged; 1e9 params", n, 16 * n, "traffic_probe_kernel",
-                lambda: q8opt.probe_adam8bit_traffic(w, g, st["m_q"], st["r_q"], tab_s, tab_u), None, keep)
+                lambda: probe(w, g, st["m_q"], st["r_q"], tab_s, tab_u), None, keep)
     if name in ("quant1b", "dequant1b"):
         n, B = 1_000_000_000, 2048
         nb = -(-n // B)

@@ -36,19 +36,27 @@
  *     multiply-add in the update formulas; divisions and square roots are
  *     correctly rounded.
  *   - Scheduling state: the step and quantize kernels hand out work through a
- *     job counter in device memory.  The library keeps a ring of 64 such
- *     counters per device (module data, nothing is allocated); every launch
- *     takes the next one and its kernel leaves it zeroed.  Launches on one
- *     stream, and up to 64 launches overlapping on different streams, are
- *     therefore independent.  A launch captured into a HIP graph keeps the
- *     counter it was given at capture time: replays of one graph are safe in
- *     sequence; do not replay it concurrently with itself, and do not let a
- *     replay overlap, on another stream, with other launches of this library
- *     (one of them may be handed the same counter).  The device entry
- *     points enqueue exactly one kernel (no memset, no copy), so they can be
- *     captured once each kernel has been launched eagerly a first time (the
- *     first launch queries occupancy and the counter address, which is not
- *     allowed during capture).
+ *     job counter in device memory (module data of the library, nothing is
+ *     allocated; a kernel leaves its counter zeroed).  Two kernels never share a
+ *     counter while either runs: eager launches use one counter per stream
+ *     (launches on one stream run in order; the per-thread default stream counts
+ *     once per host thread), launches recorded by stream capture one counter per
+ *     (capture, stream) pair that is reserved for as long as the process lives,
+ *     so a recorded graph may be replayed on any stream next to any other work
+ *     of this library.  192 streams and 64 (capture, stream) pairs per device
+ *     are served this way.  Beyond that nothing fails and nothing is shared:
+ *     when a 193rd stream appears the call synchronizes the device once and
+ *     starts its table of streams afresh, and a launch that can be given no
+ *     counter (a 65th capture; or that synchronization refused because a
+ *     capture is under way) runs its kernel with a fixed assignment of work to
+ *     workgroups, which is slower on large tensors and gives the same result.
+ *     What the caller must not do: run two instances of one recorded launch at
+ *     the same time (a graph replayed concurrently with itself, or two
+ *     executable graphs instantiated from one capture running concurrently),
+ *     or destroy a stream while a kernel of this library still runs on it.
+ *     The device entry points enqueue exactly one kernel (no memset, no copy),
+ *     so they can be captured once each kernel has been launched eagerly a
+ *     first time (the first launch queries occupancy and the counter address).
  */
 #ifndef Q8OPT_H
 #define Q8OPT_H
@@ -229,17 +237,6 @@ Q8_API q8_status q8_multi_adam8bit_step(q8_plan* plan,
                                  float weight_decay, int64_t t, int flags, void* stream);
 Q8_API q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_signed,
                                 float alpha, float beta, float weight_decay, void* stream);
-
-/*
- * Measurement aid, not part of the method: moves exactly the bytes of one
- * q8_adam8bit_step at B = 2048 (reads w, g, m_q, r_q; writes w, m_q, r_q) with the
- * same tiles, scheduler, LDS footprint and occupancy, but no arithmetic -- every
- * value is written back unchanged.  Its rate is the ceiling of the step's access
- * pattern on the chip; bench.py --workload probe1b reports it.
- */
-Q8_API q8_status q8_probe_adam8bit_traffic(float* w, const float* g, uint8_t* m_q, uint8_t* r_q,
-                                    const void* qtable_signed, const void* qtable_unsigned,
-                                    int64_t n, void* stream);
 
 #ifdef __cplusplus
 }

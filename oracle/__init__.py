@@ -32,6 +32,8 @@ def bind(L):
     L.oracle_adam8bit_step.argtypes = [fp, fp, u8p, u8p, fp, fp, fp, fp, i64, i32,
                                        f32, f32, f32, f32, f32, i64, i32]
     L.oracle_sgd8bit_step.argtypes = [fp, fp, u8p, fp, fp, i64, i32, f32, f32, f32]
+    L.oracle_adam8bit_block_normalized.argtypes = [fp, fp, u8p, u8p, f32, f32, fp, fp, i32,
+                                                   f32, f32, f32, f32, f32, i64, i32, fp, fp]
     L.oracle_adam8bit_step_bf16.argtypes = L.oracle_adam8bit_step.argtypes
     L.oracle_sgd8bit_step_bf16.argtypes = L.oracle_sgd8bit_step.argtypes
     L.oracle_adam8bit_step_f16.argtypes = L.oracle_adam8bit_step.argtypes
@@ -44,7 +46,8 @@ def bind(L):
                  "oracle_quantize_blockwise", "oracle_dequantize_blockwise", "oracle_adam32_step",
                  "oracle_sgd32_step", "oracle_adam_scalars", "oracle_adam8bit_step", "oracle_sgd8bit_step",
                  "oracle_adam8bit_step_bf16", "oracle_sgd8bit_step_bf16",
-                 "oracle_adam8bit_step_f16", "oracle_sgd8bit_step_f16"):
+                 "oracle_adam8bit_step_f16", "oracle_sgd8bit_step_f16",
+                 "oracle_adam8bit_block_normalized"):
         getattr(L, name).restype = i32
     return L
 
@@ -133,6 +136,19 @@ def adam8bit_step(w, g, m_q, r_q, N_m, N_r, q_signed, q_unsigned, B,
                                    _p(N_m, np.float32), _p(N_r, np.float32),
                                    _p(q_signed, np.float32), _p(q_unsigned, np.float32), n, B,
                                    alpha, beta1, beta2, eps, wd, t, flags))
+
+
+def adam8bit_block_normalized(w, g, m_q, r_q, N_m, N_r, q_signed, q_unsigned,
+                              alpha, beta1, beta2, eps, wd=0.0, t=1, flags=0):
+    """Normalized new states (m / N_m', r / N_r') of one block, as the 8-bit Adam step forms them
+    before the nearest-value search.  Inputs are the block's slices and its two old maxima."""
+    n = w.size
+    assert g.size == n and m_q.size == n and r_q.size == n
+    x = np.empty(n, np.float32); y = np.empty(n, np.float32)
+    _ok(lib().oracle_adam8bit_block_normalized(_p(w, np.float32), _p(g, np.float32), _p(m_q, np.uint8), _p(r_q, np.uint8),
+                                               float(N_m), float(N_r), _p(q_signed, np.float32), _p(q_unsigned, np.float32),
+                                               n, alpha, beta1, beta2, eps, wd, t, flags, _p(x, np.float32), _p(y, np.float32)))
+    return x, y
 
 
 def sgd8bit_step(w, g, m_q, N_m, q_signed, B, alpha, beta, wd=0.0):

@@ -348,6 +348,36 @@ int oracle_adam8bit_step(float *w, const float *g,
     return 0;
 }
 
+/* For the parity report: the normalized new states x = m / N_m', y = r / N_r'  */
+/* of ONE block (len <= B entries), exactly as oracle_adam8bit_step forms them   */
+/* before the nearest-value search; nothing is modified.  (0 where N' = 0.)      */
+int oracle_adam8bit_block_normalized(const float *w, const float *g,
+                                     const uint8_t *m_q, const uint8_t *r_q, float N_m, float N_r,
+                                     const float *q_signed, const float *q_unsigned, int len,
+                                     float alpha, float beta1, float beta2, float eps,
+                                     float wd, int64_t t, int flags, float *x_out, float *y_out)
+{
+    if (len < 0 || len > ORACLE_MAX_B)
+        return -1;
+    adam_scalars s = adam_prepare(alpha, beta1, beta2, eps, wd, t, flags);
+    float Nm_new = 0.0f, Nr_new = 0.0f;
+    for (int i = 0; i < len; ++i) {
+        float m_prev = q_signed[m_q[i]] * N_m;
+        float r_prev = q_unsigned[r_q[i]] * N_r;
+        float wv = w[i];
+        adam_element(&s, &wv, g[i], m_prev, r_prev, &x_out[i], &y_out[i]);
+        if (fabsf(x_out[i]) > Nm_new)
+            Nm_new = fabsf(x_out[i]);
+        if (fabsf(y_out[i]) > Nr_new)
+            Nr_new = fabsf(y_out[i]);
+    }
+    for (int i = 0; i < len; ++i) {
+        x_out[i] = (Nm_new == 0.0f) ? 0.0f : x_out[i] / Nm_new;
+        y_out[i] = (Nr_new == 0.0f) ? 0.0f : y_out[i] / Nr_new;
+    }
+    return 0;
+}
+
 int oracle_sgd8bit_step(float *w, const float *g, uint8_t *m_q, float *N_m,
                         const float *q_signed, int64_t n, int B,
                         float alpha, float beta, float wd)

@@ -1,7 +1,6 @@
 """Fused 8-bit optimizer step for MI355X (gfx950): Python binding of the C-ABI library.
 
 `from paper_2412_01195_amd import q8opt` loads the HIP library; importing this package or
-its `synth` module alone does not.  `optim` holds torch.optim front ends (Adam8bit, SGD8bit)
-that drive the library's multi-tensor entry points.
+its `synth` module alone does not.
 """
-__all__ = ["q8opt", "synth", "optim"]
+__all__ = ["q8opt", "synth"]

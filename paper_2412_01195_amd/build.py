@@ -3,7 +3,9 @@
 Five objects are compiled in parallel -- the host translation unit (entry points, quantize /
 dequantize kernels), the optimizer-step kernels once per storage type of w and g (float,
 bfloat16, binary16; same source, different -D), and the host-only table builder -- and linked
-into one shared library.
+into one shared library.  A sixth object, the benchmark's traffic probe, is linked together
+with the same five into a second library, libq8opt_probe.so, which only bench.py loads (for
+its workload probe1b); the product library does not contain it.
 """
 import os
 import shutil
@@ -15,6 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libq8opt.so")
+PROBE_LIB = os.path.join(HERE, "libq8opt_probe.so")
 HEADERS = [os.path.join(CSRC, "q8opt_internal.h"), os.path.join(CSRC, "q8opt_device.h"),
            os.path.join(ROOT, "include", "q8opt.h")]
 # (object name, source, extra defines)
@@ -25,7 +28,8 @@ UNITS = [
     ("steps_f16", os.path.join(CSRC, "q8opt_steps.hip"), ["-DQ8_STEPS_F16"]),
     ("host", os.path.join(CSRC, "q8opt_host.cpp"), []),
 ]
-SOURCES = sorted({u[1] for u in UNITS})
+PROBE_UNIT = ("probe", os.path.join(CSRC, "q8opt_probe.hip"), [])
+SOURCES = sorted({u[1] for u in UNITS + [PROBE_UNIT]})
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -43,9 +47,10 @@ def stale() -> bool:
     return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS)
 
 
-def build(force: bool = True, extra=(), out: str = LIB, jobs: int = 5) -> str:
+def build(force: bool = True, extra=(), out: str = LIB, jobs: int = 6) -> str:
     if not (force or stale()):
         return out
+    probe_out = os.path.join(os.path.dirname(out), "libq8opt_probe.so")
     tmpdir = tempfile.mkdtemp(prefix="q8opt_build_")
     try:
         def compile_unit(unit):
@@ -54,10 +59,11 @@ def build(force: bool = True, extra=(), out: str = LIB, jobs: int = 5) -> str:
             subprocess.check_call([HIPCC, *FLAGS, *extra, *defs, "-c", "-x", "hip", src, "-o", obj])
             return obj
         with ThreadPoolExecutor(max(1, jobs)) as pool:
-            objs = list(pool.map(compile_unit, UNITS))
-        tmp = out + ".tmp.%d" % os.getpid()
-        subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
-        os.replace(tmp, out)
+            objs = list(pool.map(compile_unit, UNITS + [PROBE_UNIT]))
+        for target, members in ((out, objs[:-1]), (probe_out, objs)):
+            tmp = target + ".tmp.%d" % os.getpid()
+            subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *members])
+            os.replace(tmp, target)
     finally:
         shutil.rmtree(tmpdir, ignore_errors=True)
     return out

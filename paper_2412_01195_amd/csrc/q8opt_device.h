@@ -19,10 +19,10 @@
 // reached 5.1 TB/s, chunks 5.4 TB/s, dynamic jobs of 8 x 2048 elements 5.9 TB/s and
 // dynamic jobs of 8 x 1024 elements (half the window) 6.4 TB/s.
 //
-// Barriers sit in wave-uniform branches: the waves of a workgroup may reach their
-// one exchange barrier of a job at different program points (full tile, ragged
-// tile, no tile), which is sound on this hardware because s_barrier only counts
-// arriving waves; every wave executes the same number of barriers per job.
+// Every wave of a workgroup passes the same two barrier sites per job (one in the
+// draw, one in the exchange of block maxima), whatever kind of tile it holds: a
+// tile is processed in two phases (update, then re-quantization) around the
+// exchange, and the branches on the kind of tile sit inside the phases.
 //
 // Nearest-code search (Eq. quant2): the upper 16 bits of the binary32 pattern of
 // x = m / N index a byte table in LDS that holds the code at the lower end of that
@@ -73,6 +73,7 @@ struct TileRef { int32_t tensor; int32_t tile; };
 struct AdamScalars {
     float beta1, beta2, omb1, omb2, eps, wd, alpha_t, isbc2, alpha_wd;
     int wd_mode;                          // 0 none, 1 coupled (g += wd*w), 2 decoupled
+    int bias;                             // bias-correction extension: scale the root by isbc2, step alpha_t
     int fast_ok;                          // eps and isbc2 allow the short square root / division
 };
 struct SgdScalars { float alpha, beta, wd; };
@@ -90,25 +91,20 @@ struct StepArgs {
     Sched* sched;
 };
 
-struct DeviceInfo { int cus; Sched* sched; };
-
-// Defined once, in q8opt_kernels.hip: the current device's CU count and the address of its
-// ring of job counters; the next counter of the ring.
-q8_status device_info(DeviceInfo& out);
-Sched* next_sched_slot(const DeviceInfo& di);
+// Defined once, in q8opt_kernels.hip.  device_cus: CU count of the current device.
+// acquire_sched: the job counter this launch on `stream` may use without sharing it with any
+// launch that can run at the same time, or nullptr: then the kernel walks its jobs in a
+// fixed grid-stride order and needs no counter.
+q8_status device_cus(int& cus);
+q8_status acquire_sched(hipStream_t stream, Sched** out);
 
 // Everything below has internal linkage: each translation unit instantiates only the
 // kernels it launches.
 namespace {
 
-#ifndef Q8_WG_THREADS
-#define Q8_WG_THREADS 512
-#endif
-#ifndef Q8_MIN_WAVES
-#define Q8_MIN_WAVES 4
-#endif
-constexpr int kWgThreads = Q8_WG_THREADS;
+constexpr int kWgThreads = 512;
 constexpr int kWavesPerWg = kWgThreads / 64;
+constexpr int kMinWavesPerEu = 4;         // launch bound: two workgroups per CU, up to 128 VGPRs
 constexpr int kRow = 256;                 // elements per wave row: 64 lanes x 4
 
 // Pointers into HBM carry the global address space so that loads and stores
@@ -529,42 +525,44 @@ __device__ __forceinline__ void norms_of(const uint32_t (&nbits)[NSTATE][Shape<B
 // LDS words for the exchange of wave maxima: [parity][state][wave].
 struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
 
-// Turn lane maxima into block maxima: DPP reduction inside the wave and, when a
-// block spans WPB > 1 waves, an exchange through LDS.  In that case every wave of
-// the workgroup must call this exactly once per job (it contains a barrier);
-// `parity` alternates between jobs so that one barrier per job suffices: a slot
-// is rewritten two jobs later, after barriers that every reader has passed.
+// Lane maxima -> wave-level block maxima (DPP reduction inside the wave).
 template <int B, int NSTATE>
-__device__ __forceinline__ void reduce_block_max(uint32_t (&v)[NSTATE][Shape<B>::NBLK], Exchange* ex, int parity,
-                                                 int wave, int lane)
+__device__ __forceinline__ void reduce_in_wave(uint32_t (&v)[NSTATE][Shape<B>::NBLK], int lane)
 {
     using S = Shape<B>;
 #pragma unroll
     for (int st = 0; st < NSTATE; ++st)
 #pragma unroll
         for (int k = 0; k < S::NBLK; ++k) v[st][k] = group_max<S::GROUP>(v[st][k], lane);
+}
+
+// When a block spans WPB > 1 waves, their maxima meet in LDS.  Every wave of the
+// workgroup calls this exactly once per job, with or without a tile (`have`; the
+// waves of one unit agree on it); it holds the one barrier of the exchange.
+// `parity` alternates between jobs so that one barrier per job suffices: a slot is
+// rewritten two jobs later, after barriers that every reader has passed.
+template <int B, int NSTATE>
+__device__ __forceinline__ void exchange_block_max(uint32_t (&v)[NSTATE][Shape<B>::NBLK], bool have, Exchange* ex,
+                                                   int parity, int wave, int lane)
+{
+    using S = Shape<B>;
     if (S::WPB > 1) {
-        if (lane == 0) {
+        if (have && lane == 0) {
 #pragma unroll
             for (int st = 0; st < NSTATE; ++st) ex->part[parity][st][wave] = v[st][0];
         }
         __syncthreads();
-        const int g0 = wave & ~(S::WPB - 1);
+        if (have) {
+            const int g0 = wave & ~(S::WPB - 1);
 #pragma unroll
-        for (int st = 0; st < NSTATE; ++st) {
-            uint32_t m = 0;
+            for (int st = 0; st < NSTATE; ++st) {
+                uint32_t m = 0;
 #pragma unroll
-            for (int k = 0; k < S::WPB; ++k) m = max(m, ex->part[parity][st][g0 + k]);
-            v[st][0] = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
+                for (int k = 0; k < S::WPB; ++k) m = max(m, ex->part[parity][st][g0 + k]);
+                v[st][0] = (uint32_t)__builtin_amdgcn_readfirstlane((int)m);
+            }
         }
     }
-}
-
-// The barrier of reduce_block_max for waves that have no 8-bit tile in this job.
-template <int B>
-__device__ __forceinline__ void idle_block_max()
-{
-    if (Shape<B>::WPB > 1) __syncthreads();
 }
 
 // Quantize the 4 x 4 values of this lane (Eq. quant1, quant2) against the block
@@ -617,23 +615,27 @@ __device__ __forceinline__ void requantize_store(const unsigned char* lds, float
     }
 }
 
-// Old block maximum for row r of this wave.  For B >= 256 the index is wave-uniform
-// and the value is read with a scalar load: the entry was written by an earlier
-// launch (or, later in this launch, only by a wave of this very unit after the
-// barrier), so the scalar cache cannot hold a stale copy.  Below 256 each lane
-// group reads its own block.
-#define Q8_CONSTANT __attribute__((address_space(4)))
+// Old block maxima of the block slots of this wave tile.  For B >= 256 a slot's block
+// index is the same in every lane: the value is loaded once and kept as a scalar.
+// Below 256 each lane group reads its own block.
 template <int B, bool FULL>
-__device__ __forceinline__ float load_block_max(const float* N, int64_t n, int64_t base, int r, int lane)
+__device__ __forceinline__ void load_block_maxima(const float* N, int64_t n, int64_t base, int lane,
+                                                  float (&out)[Shape<B>::NBLK])
 {
-    const int64_t row0 = base + (int64_t)r * kRow;
-    if (B >= kRow) {
-        if (!FULL && row0 >= n) return 0.0f;
-        return ((Q8_CONSTANT const float*)N)[row0 / B];
+    using S = Shape<B>;
+    gcfloat* Ng = (gcfloat*)N;
+#pragma unroll
+    for (int s = 0; s < S::NBLK; ++s) {
+        const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
+        if (B >= kRow) {
+            float v = 0.0f;
+            if (FULL || row0 < n) v = Ng[row0 / B];
+            out[s] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+        } else {
+            const int64_t e0 = row0 + lane * 4;
+            out[s] = (FULL || e0 < n) ? Ng[e0 / B] : 0.0f;
+        }
     }
-    const int64_t e0 = row0 + lane * 4;
-    if (!FULL && e0 >= n) return 0.0f;
-    return ((gcfloat*)N)[e0 / B];
 }
 
 // ---------------------------------------------------------------------------
@@ -657,15 +659,22 @@ __device__ __forceinline__ void adam_states(const AdamScalars& s, float w, float
     r_out = t3 + t5;
 }
 
-// Weight update of Eq. adam from the new 32-bit states.  FAST selects the short
-// square root and division, valid when the caller has checked the range of m and r.
-template <int WD, bool FAST>
+// Weight update of Eq. adam from the new 32-bit states.  BIAS: the bias-correction
+// extension (the root is scaled by 1/sqrt(1 - beta2^t), one product, before eps is
+// added; the step is alpha/(1 - beta1^t)); without it alpha_t == alpha.  FAST selects
+// the short square root and division, valid when the caller has checked the range of
+// m and r.
+template <int WD, bool BIAS, bool FAST>
 __device__ __forceinline__ float adam_weight(const AdamScalars& s, float w, float m, float r)
 {
     const float root = FAST ? sqrt_rn_fast(r) : sqrtf(r);
-    // without bias correction isbc2 == 1 and the fma is exactly root + eps; with it the
-    // denominator is defined as this single fused operation
-    const float d = __builtin_fmaf(root, s.isbc2, s.eps);
+    float d;
+    if (BIAS) {
+        const float rs = root * s.isbc2;
+        d = rs + s.eps;
+    } else {
+        d = root + s.eps;
+    }
     const float u = FAST ? div_rn_inrange(m, d) : m / d;
     const float t6 = s.alpha_t * u;
     if (WD == 2) {
@@ -675,13 +684,13 @@ __device__ __forceinline__ float adam_weight(const AdamScalars& s, float w, floa
     return w - t6;
 }
 
-template <int WD>
+template <int WD, bool BIAS>
 __device__ __forceinline__ void adam_element(const AdamScalars& s, float& w, float g, float m_prev,
                                              float r_prev, float& m_out, float& r_out)
 {
     float m, r;
     adam_states<WD>(s, w, g, m_prev, r_prev, m, r);
-    w = adam_weight<WD, false>(s, w, m, r);
+    w = adam_weight<WD, BIAS, false>(s, w, m, r);
     m_out = m;
     r_out = r;
 }
@@ -702,21 +711,31 @@ __device__ __forceinline__ void sgd_element(const SgdScalars& s, float& w, float
 }
 
 // ---------------------------------------------------------------------------
-// Wave tiles.  `base` = first element of this wave inside the tensor.
+// Wave tiles, in two phases around the exchange of block maxima.  `base` = first
+// element of this wave inside the tensor.  What a tile carries from the first phase
+// (update: load, dequantize, new states, new weights stored, lane maxima reduced
+// inside the wave) to the second (re-quantization and stores of codes and maxima):
+// the new states of its 4 x 4 elements per lane and the maxima of its block slots.
 // ---------------------------------------------------------------------------
-template <int B, typename WT, bool FULL, int WD>
-__device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
-                                           Exchange* ex, int parity, const AdamScalars& sc, int wave, int lane)
+template <int B, int NSTATE>
+struct Carry {
+    float val[NSTATE][kWaveRows][4];
+    uint32_t amax[NSTATE][Shape<B>::NBLK];
+};
+
+template <int B, typename WT, bool FULL, int WD, bool BIAS>
+__device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, const unsigned char* lds,
+                                             const AdamScalars& sc, int lane, Carry<B, 2>& c)
 {
     using S = Shape<B>;
     const int64_t n = d.n;
     typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
     typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
-    gbyte* m_q = (gbyte*)d.m_q;
-    gbyte* r_q = (gbyte*)d.r_q;
+    gcbyte* m_q = (gcbyte*)d.m_q;
+    gcbyte* r_q = (gcbyte*)d.r_q;
     float wv[kWaveRows][4], gv[kWaveRows][4];
     uint32_t mq[kWaveRows], rq[kWaveRows];
-    float Nm_old[kWaveRows], Nr_old[kWaveRows];
+    float Nm_old[S::NBLK], Nr_old[S::NBLK];
 #pragma unroll
     for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
@@ -731,29 +750,28 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
             for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
             mq[r] = 0; rq[r] = 0;
         }
-        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
-        Nr_old[r] = load_block_max<B, FULL>(d.N_r, n, base, r, lane);
     }
-    uint32_t amax[2][S::NBLK];
+    load_block_maxima<B, FULL>(d.N_m, n, base, lane, Nm_old);
+    load_block_maxima<B, FULL>(d.N_r, n, base, lane, Nr_old);
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) { amax[0][s] = 0; amax[1][s] = 0; }
-    // after this loop gv holds the new m and wv is reused for the new r
+    for (int s = 0; s < S::NBLK; ++s) { c.amax[0][s] = 0; c.amax[1][s] = 0; }
 #pragma unroll
     for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
+        const int slot = r / S::RPB;
         float mnew[4], rnew[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
-            const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[r]);
+            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[slot]);
+            const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[slot]);
             adam_states<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, mnew[j], rnew[j]);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
-        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], mnew);
-        amax[1][r / S::RPB] = absmax4(amax[1][r / S::RPB], rnew);
+        c.amax[0][slot] = absmax4(c.amax[0][slot], mnew);
+        c.amax[1][slot] = absmax4(c.amax[1][slot], rnew);
         // one wave-uniform test per row: every |m| and r of the row within [kFastLo, kFastHi]
         // (the running maxima bound the row from above; a row that holds an exact zero,
         // e.g. in a ragged tail, takes the general forms)
@@ -761,41 +779,48 @@ __device__ __forceinline__ void adam8_tile(const TensorDesc& d, int64_t base, in
         lo = __builtin_fminf(__builtin_fminf(lo, __builtin_fabsf(mnew[3])), rnew[0]);
         lo = __builtin_fminf(__builtin_fminf(lo, rnew[1]), rnew[2]);
         lo = __builtin_fminf(lo, rnew[3]);
-        const float hi = __builtin_fmaxf(__uint_as_float(amax[0][r / S::RPB]), __uint_as_float(amax[1][r / S::RPB]));
+        const float hi = __builtin_fmaxf(__uint_as_float(c.amax[0][slot]), __uint_as_float(c.amax[1][slot]));
         const bool general = !(lo >= kFastLo) || !(hi <= kFastHi) || !sc.fast_ok;
         if (__builtin_amdgcn_ballot_w64(general) == 0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, true>(sc, wv[r][j], mnew[j], rnew[j]);
+            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, BIAS, true>(sc, wv[r][j], mnew[j], rnew[j]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, false>(sc, wv[r][j], mnew[j], rnew[j]);
+            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, BIAS, false>(sc, wv[r][j], mnew[j], rnew[j]);
         }
         if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            gv[r][j] = mnew[j];
-            wv[r][j] = rnew[j];
+            c.val[0][r][j] = mnew[j];
+            c.val[1][r][j] = rnew[j];
         }
     }
-    reduce_block_max<B, 2>(amax, ex, parity, wave, lane);
+    reduce_in_wave<B, 2>(c.amax, lane);
+}
+
+template <int B, bool FULL>
+__device__ __forceinline__ void adam8_requantize(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
+                                                 int lane, Carry<B, 2>& c)
+{
+    using S = Shape<B>;
     BlockNorm bn[2][S::NBLK];
-    norms_of<B, 2>(amax, bn, lane);
-    requantize_store<B, FULL, false>(lds, gv, bn[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
-    requantize_store<B, FULL, true>(lds, wv, bn[1], r_q, (gfloat*)d.N_r, n, base, part, lane);
+    norms_of<B, 2>(c.amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, c.val[0], bn[0], (gbyte*)d.m_q, (gfloat*)d.N_m, d.n, base, part, lane);
+    requantize_store<B, FULL, true>(lds, c.val[1], bn[1], (gbyte*)d.r_q, (gfloat*)d.N_r, d.n, base, part, lane);
 }
 
 template <int B, typename WT, bool FULL, bool WD>
-__device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
-                                          Exchange* ex, int parity, const SgdScalars& sc, int wave, int lane)
+__device__ __forceinline__ void sgd8_update(const TensorDesc& d, int64_t base, const unsigned char* lds,
+                                            const SgdScalars& sc, int lane, Carry<B, 1>& c)
 {
     using S = Shape<B>;
     const int64_t n = d.n;
     typename Wide<WT>::ptr w = (typename Wide<WT>::ptr)d.w;
     typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
-    gbyte* m_q = (gbyte*)d.m_q;
+    gcbyte* m_q = (gcbyte*)d.m_q;
     float wv[kWaveRows][4], gv[kWaveRows][4];
     uint32_t mq[kWaveRows];
-    float Nm_old[kWaveRows];
+    float Nm_old[S::NBLK];
 #pragma unroll
     for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
@@ -809,30 +834,37 @@ __device__ __forceinline__ void sgd8_tile(const TensorDesc& d, int64_t base, int
             for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
             mq[r] = 0;
         }
-        Nm_old[r] = load_block_max<B, FULL>(d.N_m, n, base, r, lane);
     }
-    uint32_t amax[1][S::NBLK];
+    load_block_maxima<B, FULL>(d.N_m, n, base, lane, Nm_old);
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) amax[0][s] = 0;
+    for (int s = 0; s < S::NBLK; ++s) c.amax[0][s] = 0;
 #pragma unroll
     for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
+        const int slot = r / S::RPB;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[r]);
+            const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[slot]);
             float m_new;
             sgd_element<WD>(sc, wv[r][j], gv[r][j], m_prev, m_new);
             if (!FULL && j >= cnt) m_new = 0.0f;
-            gv[r][j] = m_new;
+            c.val[0][r][j] = m_new;
         }
-        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], gv[r]);
+        c.amax[0][slot] = absmax4(c.amax[0][slot], c.val[0][r]);
         if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
     }
-    reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
+    reduce_in_wave<B, 1>(c.amax, lane);
+}
+
+template <int B, bool FULL>
+__device__ __forceinline__ void sgd8_requantize(const TensorDesc& d, int64_t base, int part, const unsigned char* lds,
+                                                int lane, Carry<B, 1>& c)
+{
+    using S = Shape<B>;
     BlockNorm bn[1][S::NBLK];
-    norms_of<B, 1>(amax, bn, lane);
-    requantize_store<B, FULL, false>(lds, gv, bn[0], m_q, (gfloat*)d.N_m, n, base, part, lane);
+    norms_of<B, 1>(c.amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, c.val[0], bn[0], (gbyte*)d.m_q, (gfloat*)d.N_m, d.n, base, part, lane);
 }
 
 // Tensors that keep 32-bit states: same formulas, no quantization; one wave
@@ -858,9 +890,15 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, cons
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (ADAM) {
-                if (as.wd_mode == 1) adam_element<1>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
-                else if (as.wd_mode == 2) adam_element<2>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
-                else adam_element<0>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                if (as.bias) {
+                    if (as.wd_mode == 1) adam_element<1, true>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                    else if (as.wd_mode == 2) adam_element<2, true>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                    else adam_element<0, true>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                } else {
+                    if (as.wd_mode == 1) adam_element<1, false>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                    else if (as.wd_mode == 2) adam_element<2, false>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                    else adam_element<0, false>(as, wv[j], gv[j], mv[j], rv[j], mv[j], rv[j]);
+                }
             } else {
                 if (ss.wd != 0.0f) sgd_element<true>(ss, wv[j], gv[j], mv[j], mv[j]);
                 else sgd_element<false>(ss, wv[j], gv[j], mv[j], mv[j]);
@@ -873,40 +911,51 @@ __device__ __forceinline__ void f32_tile(const TensorDesc& d, int64_t base, cons
 }
 
 template <int B, bool FULL>
-__device__ __forceinline__ void quant_tile(gcfloat* T, gbyte* TQ, gfloat* N, int64_t n, int64_t base, int part,
-                                           const unsigned char* lds, Exchange* ex, int parity, int wave, int lane)
+__device__ __forceinline__ void quant_load(gcfloat* T, int64_t n, int64_t base, int lane, Carry<B, 1>& c)
 {
     using S = Shape<B>;
-    float v[kWaveRows][4];
-    uint32_t amax[1][S::NBLK];
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) amax[0][s] = 0;
+    for (int s = 0; s < S::NBLK; ++s) c.amax[0][s] = 0;
 #pragma unroll
     for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4f(T + e0, cnt, v[r]);
+            load4f(T + e0, cnt, c.val[0][r]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[r][j] = 0.0f;
+            for (int j = 0; j < 4; ++j) c.val[0][r][j] = 0.0f;
         }
-        amax[0][r / S::RPB] = absmax4(amax[0][r / S::RPB], v[r]);
+        c.amax[0][r / S::RPB] = absmax4(c.amax[0][r / S::RPB], c.val[0][r]);
     }
-    reduce_block_max<B, 1>(amax, ex, parity, wave, lane);
+    reduce_in_wave<B, 1>(c.amax, lane);
+}
+
+template <int B, bool FULL>
+__device__ __forceinline__ void quant_store(gbyte* TQ, gfloat* N, int64_t n, int64_t base, int part,
+                                            const unsigned char* lds, int lane, Carry<B, 1>& c)
+{
+    using S = Shape<B>;
     BlockNorm bn[1][S::NBLK];
-    norms_of<B, 1>(amax, bn, lane);
-    requantize_store<B, FULL, false>(lds, v, bn[0], TQ, N, n, base, part, lane);
+    norms_of<B, 1>(c.amax, bn, lane);
+    requantize_store<B, FULL, false>(lds, c.val[0], bn[0], TQ, N, n, base, part, lane);
 }
 
 // ---------------------------------------------------------------------------
-// Dynamic scheduling.  A job is kWavesPerWg consecutive wave tiles, i.e. UPJ
-// consecutive units.  Thread 0 of a workgroup draws job indices from
+// Scheduling.  A job is kWavesPerWg consecutive wave tiles, i.e. UPJ consecutive
+// units; workgroups are persistent and take jobs until none is left.
+//
+// Dynamic (sched != nullptr): thread 0 of a workgroup draws job indices from
 // `sched->next` and publishes them through LDS (two slots used alternately, so one
 // barrier per draw suffices).  Every workgroup leaves the loop at its first
 // out-of-range draw, without having another atomic in flight; the last one to
-// leave (counted in `sched->done`) zeroes both counters, so the slot is ready for
-// the next launch that uses it.
+// leave (counted in `sched->done`) zeroes both counters, so the counter is ready for
+// the next launch that is given it.  The host gives a counter only to launches that
+// cannot overlap with another user of the same counter.
+//
+// Static (sched == nullptr): the host had no counter to give; draw number i of
+// workgroup b is job (b + i * gridDim.x), published the same way.  Nothing is
+// shared between launches then.
 // ---------------------------------------------------------------------------
 
 struct JobBox { long long job[2]; };
@@ -918,25 +967,31 @@ struct JobBox { long long job[2]; };
 // workgroup hold a claim one draw ahead (a wider address window); the optimizer steps
 // measured faster without it, the light stand-alone quantizer faster with it.
 template <int SPAN>
-__device__ __forceinline__ void first_draw(Sched* sched, JobBox* box)
+__device__ __forceinline__ long long draw(Sched* sched, int round)
 {
-    if (threadIdx.x == 0)
-        box->job[0] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    if (sched) return (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    return ((long long)blockIdx.x + (long long)round * gridDim.x) * SPAN;
 }
 
-// `first` = this is the draw that first_draw has already issued (parity 0).
-template <int SPAN, bool AHEAD>
-__device__ __forceinline__ int64_t next_draw(Sched* sched, JobBox* box, int parity, int64_t njobs, bool first)
+template <int SPAN>
+__device__ __forceinline__ void first_draw(Sched* sched, JobBox* box)
 {
-    if (!AHEAD && !first && threadIdx.x == 0)
-        box->job[parity] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    if (threadIdx.x == 0) box->job[0] = draw<SPAN>(sched, 0);
+}
+
+// `round` = number of this draw (0 = the one first_draw has already issued); its LDS
+// slot is round & 1.
+template <int SPAN, bool AHEAD>
+__device__ __forceinline__ int64_t next_draw(Sched* sched, JobBox* box, int round, int64_t njobs)
+{
+    const int parity = round & 1;
+    if (!AHEAD && round > 0 && threadIdx.x == 0) box->job[parity] = draw<SPAN>(sched, round);
     __syncthreads();
     const long long j = box->job[parity];
     const int lo = __builtin_amdgcn_readfirstlane((int)j);
     const int hi = __builtin_amdgcn_readfirstlane((int)(j >> 32));
     const int64_t job = ((int64_t)hi << 32) | (uint32_t)lo;
-    if (AHEAD && job < njobs && threadIdx.x == 0)
-        box->job[parity ^ 1] = (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    if (AHEAD && job < njobs && threadIdx.x == 0) box->job[parity ^ 1] = draw<SPAN>(sched, round + 1);
     return job;
 }
 
@@ -950,7 +1005,7 @@ __device__ __forceinline__ bool single_draw(int64_t njobs)
 
 __device__ __forceinline__ void leave(Sched* sched)
 {
-    if (threadIdx.x == 0) {
+    if (sched && threadIdx.x == 0) {
         const unsigned long long before = atomicAdd(&sched->done, 1ULL);
         if (before == gridDim.x - 1) {
             atomicExch(&sched->next, 0ULL);
@@ -962,7 +1017,8 @@ __device__ __forceinline__ void leave(Sched* sched)
 
 // Unit -> (tensor descriptor, unit index inside the tensor).  The tables are read
 // through the constant address space with wave-uniform indices, i.e. by scalar
-// loads into SGPRs.
+// loads into SGPRs (no kernel of the library writes them).
+#define Q8_CONSTANT __attribute__((address_space(4)))
 __device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t u, int64_t& unit_in_tensor)
 {
     if (a.tiles) {
@@ -996,7 +1052,11 @@ struct Lds {
 constexpr int kStepSpan = 1;        // jobs per draw of the optimizer-step kernels
 constexpr int kQuantSpan = 4;       // the stand-alone quantizer does far less work per job
 
-template <int B, typename WT, int WD>
+// What a wave holds in one job: nothing, a tile of a tensor with 32-bit states (done in
+// the first phase), or an 8-bit tile that ends inside the tensor (full) or at its end.
+enum TileKind { kNoTile = 0, kFullTile = 1, kRaggedTile = 2 };
+
+template <int B, typename WT, int WD, bool BIAS>
 __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars& sc, Lds* lds)
 {
     using S = Shape<B>;
@@ -1007,43 +1067,54 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
     SgdScalars none{};
     const bool once = single_draw<kStepSpan>(njobs);
     int xpar = 0;
-    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
-        if (once && !first) break;
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs, first);
+    for (int round = 0;; ++round) {
+        if (once && round > 0) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, round, njobs);
         if (j0 >= njobs) break;
         for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
-            bool done = false;
+            int kind = kNoTile;
+            TensorDesc d{};
+            int64_t base = 0;
+            Carry<B, 2> c;
             if (u < a.nunits) {
                 int64_t ut;
-                const TensorDesc d = resolve(a, u, ut);
-                const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
+                d = resolve(a, u, ut);
+                base = ut * S::UNIT + (int64_t)part * kWaveElems;
                 if (d.m_f32) {
                     f32_tile<WT, true>(d, base, sc, none, lane);
                 } else if (base + kWaveElems <= d.n) {
-                    adam8_tile<B, WT, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
-                    done = true;
+                    kind = kFullTile;
+                    adam8_update<B, WT, true, WD, BIAS>(d, base, lds->tab, sc, lane, c);
                 } else {
-                    adam8_tile<B, WT, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
-                    done = true;
+                    kind = kRaggedTile;
+                    adam8_update<B, WT, false, WD, BIAS>(d, base, lds->tab, sc, lane, c);
                 }
             }
-            if (!done) idle_block_max<B>();
+            exchange_block_max<B, 2>(c.amax, kind != kNoTile, &lds->ex, xpar, wave, lane);
+            if (kind == kFullTile) adam8_requantize<B, true>(d, base, part, lds->tab, lane, c);
+            else if (kind == kRaggedTile) adam8_requantize<B, false>(d, base, part, lds->tab, lane, c);
         }
     }
 }
 
 template <int B, typename WT>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void adam8_kernel(StepArgs a, AdamScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<kStepSpan>(a.sched, &lds.box);
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     stage_second(lds.tab, a.qtab_u, threadIdx.x);
     __syncthreads();
-    if (sc.wd_mode == 0) adam8_walk<B, WT, 0>(a, sc, &lds);
-    else if (sc.wd_mode == 1) adam8_walk<B, WT, 1>(a, sc, &lds);
-    else adam8_walk<B, WT, 2>(a, sc, &lds);
+    if (sc.bias) {
+        if (sc.wd_mode == 0) adam8_walk<B, WT, 0, true>(a, sc, &lds);
+        else if (sc.wd_mode == 1) adam8_walk<B, WT, 1, true>(a, sc, &lds);
+        else adam8_walk<B, WT, 2, true>(a, sc, &lds);
+    } else {
+        if (sc.wd_mode == 0) adam8_walk<B, WT, 0, false>(a, sc, &lds);
+        else if (sc.wd_mode == 1) adam8_walk<B, WT, 1, false>(a, sc, &lds);
+        else adam8_walk<B, WT, 2, false>(a, sc, &lds);
+    }
     leave(a.sched);
 }
 
@@ -1058,34 +1129,39 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
     AdamScalars none{};
     const bool once = single_draw<kStepSpan>(njobs);
     int xpar = 0;
-    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
-        if (once && !first) break;
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, parity, njobs, first);
+    for (int round = 0;; ++round) {
+        if (once && round > 0) break;
+        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, round, njobs);
         if (j0 >= njobs) break;
         for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
-            bool done = false;
+            int kind = kNoTile;
+            TensorDesc d{};
+            int64_t base = 0;
+            Carry<B, 1> c;
             if (u < a.nunits) {
                 int64_t ut;
-                const TensorDesc d = resolve(a, u, ut);
-                const int64_t base = ut * S::UNIT + (int64_t)part * kWaveElems;
+                d = resolve(a, u, ut);
+                base = ut * S::UNIT + (int64_t)part * kWaveElems;
                 if (d.m_f32) {
                     f32_tile<WT, false>(d, base, none, sc, lane);
                 } else if (base + kWaveElems <= d.n) {
-                    sgd8_tile<B, WT, true, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
-                    done = true;
+                    kind = kFullTile;
+                    sgd8_update<B, WT, true, WD>(d, base, lds->tab, sc, lane, c);
                 } else {
-                    sgd8_tile<B, WT, false, WD>(d, base, part, lds->tab, &lds->ex, xpar, sc, wave, lane);
-                    done = true;
+                    kind = kRaggedTile;
+                    sgd8_update<B, WT, false, WD>(d, base, lds->tab, sc, lane, c);
                 }
             }
-            if (!done) idle_block_max<B>();
+            exchange_block_max<B, 1>(c.amax, kind != kNoTile, &lds->ex, xpar, wave, lane);
+            if (kind == kFullTile) sgd8_requantize<B, true>(d, base, part, lds->tab, lane, c);
+            else if (kind == kRaggedTile) sgd8_requantize<B, false>(d, base, part, lds->tab, lane, c);
         }
     }
 }
 
 template <int B, typename WT>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void sgd8_kernel(StepArgs a, SgdScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<kStepSpan>(a.sched, &lds.box);
@@ -1097,7 +1173,7 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2)
 }
 
 template <int B>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2) : Q8_MIN_WAVES)) void quantize_kernel(const void* qtab, const float* T,
+__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void quantize_kernel(const void* qtab, const float* T,
                                                                               uint8_t* TQ, float* N, int64_t n,
                                                                               int64_t nunits, Sched* sched)
 {
@@ -1111,88 +1187,30 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? (kWgThreads > 512 ? 3 : 2)
     const int part = wave % S::WPB;
     const int64_t njobs = (nunits + S::UPJ - 1) / S::UPJ;
     int xpar = 0;
-    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
-        const int64_t j0 = next_draw<kQuantSpan, true>(sched, &lds.box, parity, njobs, first);
+    for (int round = 0;; ++round) {
+        const int64_t j0 = next_draw<kQuantSpan, true>(sched, &lds.box, round, njobs);
         if (j0 >= njobs) break;
         for (int k = 0; k < kQuantSpan && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
+            const int64_t base = u * S::UNIT + (int64_t)part * kWaveElems;
+            int kind = kNoTile;
+            Carry<B, 1> c;
             if (u < nunits) {
-                const int64_t base = u * S::UNIT + (int64_t)part * kWaveElems;
-                if (base + kWaveElems <= n)
-                    quant_tile<B, true>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, &lds.ex, xpar, wave, lane);
-                else
-                    quant_tile<B, false>((gcfloat*)T, (gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, &lds.ex, xpar, wave, lane);
-            } else {
-                idle_block_max<B>();
+                if (base + kWaveElems <= n) {
+                    kind = kFullTile;
+                    quant_load<B, true>((gcfloat*)T, n, base, lane, c);
+                } else {
+                    kind = kRaggedTile;
+                    quant_load<B, false>((gcfloat*)T, n, base, lane, c);
+                }
             }
+            exchange_block_max<B, 1>(c.amax, kind != kNoTile, &lds.ex, xpar, wave, lane);
+            if (kind == kFullTile) quant_store<B, true>((gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, lane, c);
+            else if (kind == kRaggedTile) quant_store<B, false>((gbyte*)TQ, (gfloat*)N, n, base, part, lds.tab, lane, c);
         }
     }
     leave(sched);
 }
-
-#ifdef Q8_WITH_TRAFFIC_PROBE      // compiled into the host translation unit only
-// Measurement aid: the memory traffic of one Adam (8-bit) step at B = 2048 -- same wave
-// tiles, same scheduler, same LDS footprint and occupancy, same one barrier per job --
-// with the arithmetic left out: w and both code arrays are written back unchanged, g is
-// only read.  Its rate is what this access pattern can reach on the chip.
-__global__ __launch_bounds__(kWgThreads, Q8_MIN_WAVES) void traffic_probe_kernel(StepArgs a)
-{
-    using S = Shape<2048>;
-    __shared__ __attribute__((aligned(16))) Lds lds;
-    first_draw<kStepSpan>(a.sched, &lds.box);
-    stage_first(lds.tab, a.qtab_s, threadIdx.x);
-    stage_second(lds.tab, a.qtab_u, threadIdx.x);
-    __syncthreads();
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int part = wave % S::WPB;
-    const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
-    const int64_t n = a.single.n;
-    gfloat* w = (gfloat*)a.single.w;
-    gcfloat* g = (gcfloat*)a.single.g;
-    gbyte* m_q = (gbyte*)a.single.m_q;
-    gbyte* r_q = (gbyte*)a.single.r_q;
-    const bool once = single_draw<kStepSpan>(njobs);
-    for (int parity = 0, first = 1;; parity ^= 1, first = 0) {
-        if (once && !first) break;
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds.box, parity, njobs, first);
-        if (j0 >= njobs) break;
-        const int64_t u = j0 * S::UPJ + wave / S::WPB;
-        const int64_t base = u * S::UNIT + (int64_t)part * kWaveElems;
-        float wv[kWaveRows][4], gv[kWaveRows][4];
-        uint32_t mq[kWaveRows], rq[kWaveRows];
-        int cnt[kWaveRows];
-#pragma unroll
-        for (int r = 0; r < kWaveRows; ++r) {
-            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
-            cnt[r] = (u < a.nunits) ? lane_count(n, e0) : 0;
-            if (cnt[r] > 0) {
-                load4f(w + e0, cnt[r], wv[r]);
-                load4f(g + e0, cnt[r], gv[r]);
-                mq[r] = load4b(m_q + e0, cnt[r]);
-                rq[r] = load4b(r_q + e0, cnt[r]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) asm volatile("" ::"v"(gv[r][j]));      // keep the loads of g
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < kWaveRows; ++r) {
-            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
-            if (cnt[r] > 0) store4f(w + e0, cnt[r], wv[r]);
-        }
-        __syncthreads();                               // stands for the exchange of block maxima
-#pragma unroll
-        for (int r = 0; r < kWaveRows; ++r) {
-            const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
-            if (cnt[r] > 0) {
-                store4b(m_q + e0, cnt[r], mq[r]);
-                store4b(r_q + e0, cnt[r], rq[r]);
-            }
-        }
-    }
-    leave(a.sched);
-}
-#endif
 
 // ---------------------------------------------------------------------------
 // Launch helpers (host).
@@ -1203,10 +1221,10 @@ __global__ __launch_bounds__(kWgThreads, Q8_MIN_WAVES) void traffic_probe_kernel
 // `per_cu` caches the occupancy query of one kernel (0 = not asked yet; the
 // answer is the same on every device of one model, so one cache serves all).
 template <typename K>
-q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, int& grid, Sched** slot)
+q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, hipStream_t stream, int& grid, Sched** slot)
 {
-    DeviceInfo di;
-    q8_status st = device_info(di);
+    int cus = 0;
+    q8_status st = device_cus(cus);
     if (st != Q8_OK) return st;
     int occ = per_cu.load(std::memory_order_relaxed);
     if (occ <= 0) {
@@ -1215,11 +1233,10 @@ q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, int& grid,
         per_cu.store(occ, std::memory_order_relaxed);
     }
     int64_t want = njobs;
-    int64_t cap = (int64_t)di.cus * occ;
+    int64_t cap = (int64_t)cus * occ;
     grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
-    *slot = next_sched_slot(di);
-    return Q8_OK;
+    return acquire_sched(stream, slot);
 }
 
 inline q8_status launch_status()
@@ -1244,7 +1261,7 @@ q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 {
     static std::atomic<int> per_cu{0};
     int grid;
-    q8_status st = grid_for(adam8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
+    q8_status st = grid_for(adam8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &a.sched);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL((adam8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
@@ -1255,7 +1272,7 @@ q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 {
     static std::atomic<int> per_cu{0};
     int grid;
-    q8_status st = grid_for(sgd8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &a.sched);
+    q8_status st = grid_for(sgd8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &a.sched);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL((sgd8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
@@ -1268,24 +1285,11 @@ q8_status launch_quantize(const void* qtab, const float* T, uint8_t* TQ, float* 
     static std::atomic<int> per_cu{0};
     int grid;
     Sched* slot = nullptr;
-    q8_status st = grid_for(quantize_kernel<B>, per_cu, (nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, grid, &slot);
+    q8_status st = grid_for(quantize_kernel<B>, per_cu, (nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &slot);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL(quantize_kernel<B>, dim3(grid), dim3(kWgThreads), 0, stream, qtab, T, TQ, N, n, nunits, slot);
     return launch_status();
 }
-
-#ifdef Q8_WITH_TRAFFIC_PROBE
-inline q8_status launch_traffic_probe(StepArgs a, hipStream_t stream)
-{
-    static std::atomic<int> per_cu{0};
-    int grid;
-    q8_status st = grid_for(traffic_probe_kernel, per_cu, (a.nunits + Shape<2048>::UPJ - 1) / Shape<2048>::UPJ, grid,
-                            &a.sched);
-    if (st != Q8_OK) return st;
-    hipLaunchKernelGGL(traffic_probe_kernel, dim3(grid), dim3(kWgThreads), 0, stream, a);
-    return launch_status();
-}
-#endif
 
 }  // namespace
 }  // namespace q8

@@ -2,7 +2,6 @@
 // the kernels that do not depend on the storage type of w and g (stand-alone quantize and
 // dequantize).  The optimizer-step kernels are instantiated in q8opt_steps.hip, once per
 // storage type.
-#define Q8_WITH_TRAFFIC_PROBE
 #include "q8opt_device.h"
 
 #include <math.h>
@@ -22,44 +21,121 @@ q8_status run_sgd_bf16(int B, StepArgs a, const SgdScalars& sc, hipStream_t stre
 q8_status run_adam_f16(int B, StepArgs a, const AdamScalars& sc, hipStream_t stream);
 q8_status run_sgd_f16(int B, StepArgs a, const SgdScalars& sc, hipStream_t stream);
 
-// Job counters of the dynamic scheduler: a ring of slots in device memory that
-// launches use in turn.  A kernel leaves its slot zeroed, so consecutive launches
-// on one stream may share a slot; launches that overlap on different streams get
-// different slots unless more than kSchedSlots of them are in flight at once.
-constexpr int kSchedSlots = 64;
-__device__ Sched g_sched[kSchedSlots];
+// Job counters of the dynamic scheduler (device memory that belongs to the library: module
+// data, nothing is allocated).  A kernel leaves its counter zeroed.  Two kernels must never
+// use one counter at the same time, so a counter is tied to what orders its users:
+//   - eager launches: one counter per stream (launches on one stream run in order); the
+//     per-thread default stream counts as one stream per host thread.  When more streams
+//     have been seen than there are counters, the device is synchronized once (nothing is
+//     in flight then) and the table starts again;
+//   - launches recorded by stream capture: one counter per (capture, stream) pair, reserved
+//     for good, because the recorded graph can be replayed later on any stream; launches
+//     recorded from one stream in one capture run in order in every replay.
+// When no counter can be given (the reserved ones are used up, or the device cannot be
+// synchronized because some stream is being captured), the launch gets none and its
+// kernel walks the jobs in a fixed order instead: slower on large tensors, never wrong.
+constexpr int kEagerSlots = 192;
+constexpr int kGraphSlots = 64;
+__device__ Sched g_sched[kEagerSlots + kGraphSlots];
 
+struct SlotKey { hipStream_t stream; unsigned long long id; };
 
 // One record per device, filled on the first call with that device current
 // (every GPU holds its own copy of g_sched at its own address).  Host threads
 // may call the library concurrently.
+struct DeviceRec {
+    int cus;                         // 0: not asked yet
+    Sched* sched;
+    int eager_used, graph_used;
+    SlotKey eager[kEagerSlots];
+    SlotKey graph[kGraphSlots];
+};
 constexpr int kMaxDevices = 64;
 std::mutex g_dev_mutex;
-DeviceInfo g_dev[kMaxDevices];      // cus == 0: not asked yet
+DeviceRec g_dev[kMaxDevices];
 
-q8_status device_info(DeviceInfo& out)
+// caller holds g_dev_mutex
+q8_status device_rec(DeviceRec** out)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Q8_ELAUNCH;
-    std::lock_guard<std::mutex> lock(g_dev_mutex);
-    DeviceInfo& di = g_dev[dev];
-    if (di.cus == 0) {
+    DeviceRec& r = g_dev[dev];
+    if (r.cus == 0) {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
             return Q8_ELAUNCH;
         void* p = nullptr;
         if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_sched)) != hipSuccess || !p) return Q8_ELAUNCH;
-        di.sched = static_cast<Sched*>(p);
-        di.cus = cus;
+        r.sched = static_cast<Sched*>(p);
+        r.cus = cus;
     }
-    out = di;
+    *out = &r;
     return Q8_OK;
 }
 
-Sched* next_sched_slot(const DeviceInfo& di)
+q8_status device_cus(int& cus)
 {
-    static std::atomic<unsigned> turn{0};
-    return di.sched + (turn.fetch_add(1) % kSchedSlots);
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    DeviceRec* r = nullptr;
+    q8_status st = device_rec(&r);
+    if (st == Q8_OK) cus = r->cus;
+    return st;
+}
+
+// small unique number of the calling host thread (keys the per-thread default stream)
+unsigned long long thread_tag()
+{
+    static std::atomic<unsigned long long> next{1};
+    thread_local unsigned long long mine = next.fetch_add(1);
+    return mine;
+}
+
+int find_key(const SlotKey* keys, int used, const SlotKey& k)
+{
+    for (int i = 0; i < used; ++i)
+        if (keys[i].stream == k.stream && keys[i].id == k.id) return i;
+    return -1;
+}
+
+q8_status acquire_sched(hipStream_t stream, Sched** out)
+{
+    *out = nullptr;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    unsigned long long cap_id = 0;
+    if (hipStreamGetCaptureInfo(stream, &cap, &cap_id) != hipSuccess) {
+        (void)hipGetLastError();
+        return Q8_ELAUNCH;
+    }
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    DeviceRec* r = nullptr;
+    q8_status st = device_rec(&r);
+    if (st != Q8_OK) return st;
+    if (cap != hipStreamCaptureStatusNone) {
+        if (cap != hipStreamCaptureStatusActive) return Q8_ELAUNCH;          // an invalidated capture
+        const SlotKey k{stream, cap_id};
+        int i = find_key(r->graph, r->graph_used, k);
+        if (i < 0 && r->graph_used < kGraphSlots) {
+            i = r->graph_used++;
+            r->graph[i] = k;
+        }
+        if (i >= 0) *out = r->sched + kEagerSlots + i;
+        return Q8_OK;                                                        // else: fixed order
+    }
+    const SlotKey k{stream, stream == hipStreamPerThread ? thread_tag() : 0ULL};
+    int i = find_key(r->eager, r->eager_used, k);
+    if (i < 0) {
+        if (r->eager_used == kEagerSlots) {
+            if (hipDeviceSynchronize() != hipSuccess) {
+                (void)hipGetLastError();
+                return Q8_OK;                                                // fixed order
+            }
+            r->eager_used = 0;
+        }
+        i = r->eager_used++;
+        r->eager[i] = k;
+    }
+    *out = r->sched + i;
+    return Q8_OK;
 }
 
 }  // namespace q8
@@ -71,10 +147,7 @@ namespace {
 // element is (index >> log2 B).  Launched flat (one workgroup per 4096 elements),
 // so the hardware dispatcher hands the chunks out in address order (4 steps measured
 // best among 1, 2, 4, 8, 16).
-#ifndef Q8_DQ_STEPS
-#define Q8_DQ_STEPS 4
-#endif
-constexpr int kDequantSteps = Q8_DQ_STEPS;
+constexpr int kDequantSteps = 4;
 constexpr int kDequantChunk = 1024 * kDequantSteps;
 
 __global__ __launch_bounds__(256) void dequantize_kernel(const void* qtab, const uint8_t* TQ_, const float* N_,
@@ -147,7 +220,8 @@ q8_status make_adam_scalars(float alpha, float beta1, float beta2, float eps, fl
     s.omb2 = 1.0f - beta2;
     s.alpha_t = alpha;
     s.isbc2 = 1.0f;
-    if (flags & Q8_FLAG_BIAS_CORRECTION) {
+    s.bias = (flags & Q8_FLAG_BIAS_CORRECTION) ? 1 : 0;
+    if (s.bias) {
         if (t < 1) return Q8_EINVAL;
         // beta^t in binary64 by left-to-right square-and-multiply
         auto ipow = [](double base, int64_t e) {
@@ -296,24 +370,6 @@ extern "C" q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t
         int64_t n, int B, float alpha, float beta, float weight_decay, void* stream)
 {
     return sgd_step(kStoreF16, w, g, m_q, N_m, qtable_signed, n, B, alpha, beta, weight_decay, stream);
-}
-
-extern "C" q8_status q8_probe_adam8bit_traffic(float* w, const float* g, uint8_t* m_q, uint8_t* r_q,
-                                               const void* qtable_signed, const void* qtable_unsigned, int64_t n,
-                                               void* stream)
-{
-    if (n < 0) return Q8_EINVAL;
-    if (n == 0) return Q8_OK;
-    if (!w || !g || !m_q || !r_q || !qtable_signed || !qtable_unsigned) return Q8_EINVAL;
-    if (!aligned(w, 16) || !aligned(g, 16) || !aligned(m_q, 4) || !aligned(r_q, 4) || !aligned(qtable_signed, 16) ||
-        !aligned(qtable_unsigned, 16))
-        return Q8_EALIGN;
-    StepArgs a{};
-    a.single = TensorDesc{w, g, m_q, r_q, nullptr, nullptr, nullptr, nullptr, n};
-    a.nunits = (n + 2047) / 2048;
-    a.qtab_s = qtable_signed;
-    a.qtab_u = qtable_unsigned;
-    return launch_traffic_probe(a, static_cast<hipStream_t>(stream));
 }
 
 namespace {

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("Q8OPT_LIB", os.path.join(_HERE, "libq8opt.so"))   # override: another build of the library
+LIB_PATH = os.path.join(_HERE, "libq8opt.so")
 
 FLAG_BIAS_CORRECTION = 1
 FLAG_DECOUPLED_WD = 2
@@ -27,7 +27,6 @@ EXPORTS = (
     "q8_plan_create", "q8_plan_destroy", "q8_multi_adam8bit_step", "q8_multi_sgd8bit_step",
     "q8_adam8bit_step_bf16", "q8_sgd8bit_step_bf16", "q8_plan_create_bf16",
     "q8_adam8bit_step_f16", "q8_sgd8bit_step_f16", "q8_plan_create_f16",
-    "q8_probe_adam8bit_traffic",
 )
 
 
@@ -67,7 +66,6 @@ def lib():
         L.q8_sgd8bit_step_bf16.argtypes = L.q8_sgd8bit_step.argtypes
         L.q8_adam8bit_step_f16.argtypes = L.q8_adam8bit_step.argtypes
         L.q8_sgd8bit_step_f16.argtypes = L.q8_sgd8bit_step.argtypes
-        L.q8_probe_adam8bit_traffic.argtypes = [vp, vp, vp, vp, vp, vp, i64, vp]
         L.q8_plan_create.argtypes = [C.POINTER(q8_tensor), i32, i32, C.POINTER(vp)]
         L.q8_plan_create_bf16.argtypes = L.q8_plan_create.argtypes
         L.q8_plan_create_f16.argtypes = L.q8_plan_create.argtypes
@@ -205,14 +203,6 @@ def sgd8bit_step_f16(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight_
                      n: Optional[int] = None):
     """w, g: torch.float16 tensors."""
     _sgd("q8_sgd8bit_step_f16", "float16", w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n)
-
-
-def probe_adam8bit_traffic(w, g, m_q, r_q, qtable_signed, qtable_unsigned, n: Optional[int] = None):
-    """Measurement aid: the step's memory traffic without its arithmetic (values unchanged)."""
-    n = w.numel() if n is None else n
-    _check(lib().q8_probe_adam8bit_traffic(_ptr(w, "float32"), _ptr(g, "float32"), _ptr(m_q, "uint8"), _ptr(r_q, "uint8"),
-                                           _ptr(qtable_signed, "uint8"), _ptr(qtable_unsigned, "uint8"), n, _stream()),
-           "q8_probe_adam8bit_traffic")
 
 
 class Plan:

@@ -10,3 +10,12 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Parity reports of the whole-tensor tests (mismatch counts), shown for passing runs too."""
+    from tests import harness
+    if harness.REPORT_LINES:
+        terminalreporter.write_sep("-", "parity reports")
+        for line in harness.REPORT_LINES:
+            terminalreporter.write_line(line)

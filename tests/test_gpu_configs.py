@@ -2,10 +2,11 @@
 
 Small configurations (1-3 and a reduced 5) are compared element by element after every
 step with host-generated inputs.  The full-size configurations 4 (10^9 parameters) and 5
-(64 x 1 562 500, B = 256, heavy-tailed gradients) use device-generated seeded inputs; the
-oracle follows a sample of blocks (blocks are independent, so a block's trajectory needs
-only its own weights, gradients and state) and whole-tensor properties are checked on the
-device."""
+(64 x 1 562 500, B = 256, heavy-tailed gradients) use device-generated seeded inputs and are
+compared with the oracle over EVERY entry after EVERY step (the oracle's block ranges run on
+all host threads), with the mismatch count reported; a quicker tier follows a sample of
+blocks (blocks are independent, so a block's trajectory needs only its own weights,
+gradients and state)."""
 import numpy as np
 import pytest
 
@@ -370,3 +371,47 @@ def test_config5_full_size_sampled(q8, tabs):
         check_block_properties("config 5 tensor %d" % i, ds[i], n, B)
     plan.destroy()
     print("config 5: max parameter relative error %.3g" % worst)
+
+
+# ------------------------------------------------------------------ full size, every entry, every step
+def test_config4_one_billion_parameters_every_entry(q8, tabs):
+    """Config 4 in the benchmark's launch configuration: one flat tensor of 10^9 parameters
+    (488 282 blocks, the last 512 long), Adam, B = 2048, 5 steps.  The oracle advances all
+    blocks; codes, block maxima and weights of the whole tensor are compared after each step."""
+    n, B = 1_000_000_000, 2048
+    gen = torch.Generator(device="cuda"); gen.manual_seed(4)
+    w = torch.empty(n, device="cuda").uniform_(-0.1, 0.1, generator=gen)
+    g = torch.empty(n, device="cuda")
+    d = device_state(n, B)
+    chk = H.WholeTensorParity("config 4", w, B)
+    for t in range(1, 6):
+        g.normal_(0.0, 1e-3, generator=gen)
+        chk.oracle_step(g, t)
+        q8.adam8bit_step(w, g, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        bad = chk.compare(w, d, "config 4 step %d" % t)
+        print("config 4 step %d: %d mismatching codes" % (t, bad), flush=True)
+    H.report_parity("config 4 (1e9 parameters, B=2048, 5 steps, every entry after every step)", [chk])
+
+
+def test_config5_full_size_every_entry(q8, tabs):
+    """Config 5 at full size in one multi-tensor launch per step: 64 tensors x 1 562 500
+    parameters, Adam, B = 256 (last block 132 long), Student-t gradients with per-tensor scales
+    1e-6..1e-1 and 1 % outliers x100, 50 steps; every entry compared after every step."""
+    nt, n, B = 64, 1_562_500, 256
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    ws = [torch.empty(n, device="cuda").uniform_(-0.1, 0.1, generator=gen) for _ in range(nt)]
+    gs = [torch.empty(n, device="cuda") for _ in range(nt)]
+    ds = [device_state(n, B) for _ in range(nt)]
+    scales = [synth.heavy_tail_scale(5, i) for i in range(nt)]
+    plan = q8.Plan([dict(w=ws[i], g=gs[i], **ds[i]) for i in range(nt)], B)
+    chks = [H.WholeTensorParity("config 5 tensor %d" % i, ws[i], B) for i in range(nt)]
+    for t in range(1, 51):
+        for i in range(nt):
+            gs[i].copy_(heavy_tail_grad_device(n, B, scales[i], gen))
+        list(H.pool().map(lambda i: chks[i].oracle_step(gs[i], t, split=False), range(nt)))
+        plan.multi_adam8bit_step(tabs[0], tabs[1], **H.ADAM, t=t)
+        bad = sum(chks[i].compare(ws[i], ds[i], "config 5 tensor %d step %d" % (i, t)) for i in range(nt))
+        if t % 10 == 0 or bad:
+            print("config 5 step %d: %d mismatching codes" % (t, bad), flush=True)
+    plan.destroy()
+    H.report_parity("config 5 (64 x 1 562 500 parameters, B=256, 50 steps, every entry after every step)", chks)

@@ -414,13 +414,16 @@ def test_host_threads_launch_concurrently(q8, tabs):
 
 
 def test_traffic_probe_leaves_everything_unchanged(q8, tabs):
-    """The measurement aid rewrites w and both code arrays with the values it read."""
+    """The benchmark's measurement aid (a library of its own, not the product's) rewrites w and
+    both code arrays with the values it read."""
+    import bench
+    probe = bench.load_traffic_probe()
     n = 2048 * 9 + 777
     rng = np.random.default_rng(3)
     w0 = rng.standard_normal(n).astype(np.float32); g0 = rng.standard_normal(n).astype(np.float32)
     m0 = rng.integers(0, 256, n, dtype=np.uint8); r0 = rng.integers(0, 256, n, dtype=np.uint8)
     w, g, m, r = dev(w0), dev(g0), dev(m0), dev(r0)
-    q8.probe_adam8bit_traffic(w, g, m, r, tabs[0], tabs[1])
-    q8.probe_adam8bit_traffic(w, g, m, r, tabs[0], tabs[1])
+    probe(w, g, m, r, tabs[0], tabs[1])
+    probe(w, g, m, r, tabs[0], tabs[1])
     assert np.array_equal(w.cpu().numpy().view(np.uint32), w0.view(np.uint32)) and np.array_equal(g.cpu().numpy(), g0)
     assert np.array_equal(m.cpu().numpy(), m0) and np.array_equal(r.cpu().numpy(), r0)

@@ -60,8 +60,8 @@ MUTATIONS = [
     ("sgd decay after the momentum", [("    float t1 = beta * m_prev;\n    float m = t1 + g;",
                                        "    float t1 = beta * m_prev;\n    float m = t1 + g;\n    if (wd != 0.0f) m = m + wd * wv;")],
      [OPTIM]),
-    ("second state searched in the signed map", [("quantize_block(q_unsigned, rbuf, len, r_q + st, N_r + b);\n    }\n    return 0;\n}\n\nint oracle_sgd8bit_step",
-                                                  "quantize_block(q_signed, rbuf, len, r_q + st, N_r + b);\n    }\n    return 0;\n}\n\nint oracle_sgd8bit_step")],
+    ("second state searched in the signed map", [("quantize_block(q_unsigned, rbuf, len, r_q + st, N_r + b);\n    }\n    return 0;\n}\n\n/* For the parity report",
+                                                  "quantize_block(q_signed, rbuf, len, r_q + st, N_r + b);\n    }\n    return 0;\n}\n\n/* For the parity report")],
      [OPTIM]),
     # --- Eq. quant1 - quant3
     ("normalisation by reciprocal multiply", [("float x = T[i] / N;", "float x = T[i] * (1.0f / N);")], [QUANT] + NOT_SEARCH),
