@@ -78,8 +78,9 @@ enum {
     Q8_EBLOCK = -3,     /* B is not a power of two in [64, 4096]             */
     Q8_ELAUNCH = -4,    /* the HIP runtime refused the launch or a copy      */
     Q8_ENOMEM = -5,     /* q8_plan_create could not allocate its table       */
-    Q8_ECODEBOOK = -6   /* codebook not strictly increasing within [-1, 1],
+    Q8_ECODEBOOK = -6,  /* codebook not strictly increasing within [-1, 1],
                            or too fine for the search table                  */
+    Q8_ELIMIT = -7      /* list too large for q8_multi_adam8bit_step_noalloc */
 };
 
 /* flags of the Adam entry points; 0 = Eq. adam exactly as printed            */
@@ -237,6 +238,30 @@ Q8_API q8_status q8_multi_adam8bit_step(q8_plan* plan,
                                  float weight_decay, int64_t t, int flags, void* stream);
 Q8_API q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_signed,
                                 float alpha, float beta, float weight_decay, void* stream);
+
+/*
+ * For callers that cannot allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid it: q8_multi_adam8bit_step without a
+ * plan.  Same update, same results as q8_plan_create + q8_multi_adam8bit_step on
+ * the same list (w and g binary32), but the tables a plan keeps in memory it
+ * allocated (tensor descriptors, unit table) and the job counter live in a static
+ * device array of the library (1 122 560 bytes per GPU, held until the process
+ * ends).  `list` is host memory and is consumed before the call returns (it
+ * travels inside kernel arguments); the call enqueues only kernels on `stream`
+ * (ceil(count / 40) small table-fill launches, then the step): no hipMalloc, no
+ * hipFree, no memset, no copy, so it may be recorded by stream capture.
+ * Limits: count <= 1024 tensors and at most 131 072 units of max(B, 1024)
+ * elements in total (e.g. 134 million parameters at B <= 1024, 268 million at
+ * B = 2048), else Q8_ELIMIT and nothing is enqueued.  All calls on one GPU share
+ * the one array: calls that overlap in time on one GPU (two streams, or a graph
+ * replayed next to an eager call) race and give wrong results; calls on one
+ * stream, or otherwise ordered, are safe.  Other arguments and errors as for
+ * q8_plan_create and q8_multi_adam8bit_step.
+ */
+Q8_API q8_status q8_multi_adam8bit_step_noalloc(const q8_tensor* list /* host */, int count, int B,
+                                         const void* qtable_signed, const void* qtable_unsigned,
+                                         float alpha, float beta1, float beta2, float eps,
+                                         float weight_decay, int64_t t, int flags, void* stream);
 
 #ifdef __cplusplus
 }

@@ -1017,7 +1017,7 @@ __device__ __forceinline__ void leave(Sched* sched)
 
 // Unit -> (tensor descriptor, unit index inside the tensor).  The tables are read
 // through the constant address space with wave-uniform indices, i.e. by scalar
-// loads into SGPRs (no kernel of the library writes them).
+// loads into SGPRs (they are complete before the launch that reads them starts).
 #define Q8_CONSTANT __attribute__((address_space(4)))
 __device__ __forceinline__ TensorDesc resolve(const StepArgs& a, int64_t u, int64_t& unit_in_tensor)
 {
@@ -1220,6 +1220,8 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void 
 // occupancy, never more than there are jobs.
 // `per_cu` caches the occupancy query of one kernel (0 = not asked yet; the
 // answer is the same on every device of one model, so one cache serves all).
+// `*slot` != nullptr on entry: the caller brings its own counter; otherwise one is acquired
+// for `stream` (possibly none: fixed order).
 template <typename K>
 q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, hipStream_t stream, int& grid, Sched** slot)
 {
@@ -1236,7 +1238,7 @@ q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, hipStream_
     int64_t cap = (int64_t)cus * occ;
     grid = (int)(want < cap ? want : cap);
     if (grid < 1) grid = 1;
-    return acquire_sched(stream, slot);
+    return *slot ? Q8_OK : acquire_sched(stream, slot);
 }
 
 inline q8_status launch_status()

@@ -19,6 +19,7 @@ extern "C" const char* q8_status_str(q8_status s)
     case Q8_ELAUNCH: return "Q8_ELAUNCH: HIP launch or copy failed";
     case Q8_ENOMEM: return "Q8_ENOMEM: device allocation failed";
     case Q8_ECODEBOOK: return "Q8_ECODEBOOK: unusable codebook";
+    case Q8_ELIMIT: return "Q8_ELIMIT: list exceeds the static workspace (1024 tensors, 131072 units)";
     default: return "unknown q8_status";
     }
 }

@@ -374,6 +374,27 @@ extern "C" q8_status q8_sgd8bit_step_f16(uint16_t* w, const uint16_t* g, uint8_t
 
 namespace {
 
+// Argument rules of one list entry; nt = its number of units of `te` elements.
+q8_status check_tensor(const q8_tensor& t, size_t wg_al, int64_t te, int64_t& nt, bool& has_r)
+{
+    nt = 0;
+    if (t.n < 0) return Q8_EINVAL;
+    if (t.n == 0) return Q8_OK;                       // an empty tensor contributes no unit; its pointers are not looked at
+    if (!t.w || !t.g) return Q8_EINVAL;
+    if (!aligned(t.w, wg_al) || !aligned(t.g, wg_al)) return Q8_EALIGN;
+    if (t.m_f32) {
+        if (!aligned(t.m_f32, 16) || !aligned(t.r_f32, 16)) return Q8_EALIGN;
+        if (!t.r_f32) has_r = false;
+    } else {
+        if (!t.m_q || !t.N_m) return Q8_EINVAL;
+        if (!aligned(t.m_q, 4) || !aligned(t.N_m, 4) || !aligned(t.r_q, 4) || !aligned(t.N_r, 4)) return Q8_EALIGN;
+        if (!t.r_q || !t.N_r) has_r = false;
+    }
+    nt = (t.n + te - 1) / te;
+    if (nt > INT32_MAX) return Q8_EINVAL;
+    return Q8_OK;
+}
+
 q8_status plan_create(const q8_tensor* list, int count, int B, Store store, q8_plan** out)
 {
     if (!out) return Q8_EINVAL;
@@ -385,21 +406,9 @@ q8_status plan_create(const q8_tensor* list, int count, int B, Store store, q8_p
     int64_t ntiles = 0;
     bool has_r = true;
     for (int i = 0; i < count; ++i) {
-        const q8_tensor& t = list[i];
-        if (t.n < 0) return Q8_EINVAL;
-        if (t.n == 0) continue;                       // an empty tensor contributes no unit; its pointers are not looked at
-        if (!t.w || !t.g) return Q8_EINVAL;
-        if (!aligned(t.w, wg_al) || !aligned(t.g, wg_al)) return Q8_EALIGN;
-        if (t.m_f32) {
-            if (!aligned(t.m_f32, 16) || !aligned(t.r_f32, 16)) return Q8_EALIGN;
-            if (!t.r_f32) has_r = false;
-        } else {
-            if (!t.m_q || !t.N_m) return Q8_EINVAL;
-            if (!aligned(t.m_q, 4) || !aligned(t.N_m, 4) || !aligned(t.r_q, 4) || !aligned(t.N_r, 4)) return Q8_EALIGN;
-            if (!t.r_q || !t.N_r) has_r = false;
-        }
-        const int64_t nt = (t.n + te - 1) / te;
-        if (nt > INT32_MAX) return Q8_EINVAL;
+        int64_t nt = 0;
+        q8_status st = check_tensor(list[i], wg_al, te, nt, has_r);
+        if (st != Q8_OK) return st;
         ntiles += nt;
     }
     TensorDesc* h_descs = new (std::nothrow) TensorDesc[count];
@@ -498,4 +507,128 @@ extern "C" q8_status q8_multi_sgd8bit_step(q8_plan* plan, const void* qtable_sig
     a.qtab_s = qtable_signed;
     const SgdScalars sc{alpha, beta, weight_decay};
     return run_sgd(plan->store, plan->B, a, sc, static_cast<hipStream_t>(stream));
+}
+
+// ---------------------------------------------------------------------------
+// Multi-tensor Adam step for callers that cannot allocate: the tables a q8_plan keeps in
+// allocated device memory (tensor descriptors, unit table) and the job counter live in one
+// static device array instead.  The host list travels to the device inside kernel arguments,
+// a chunk of descriptors per launch of a small fill kernel, so the call enqueues kernels
+// only: no allocation, no memset, no copy.
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr int kNoallocMaxTensors = 1024;
+constexpr int kNoallocMaxUnits = 1 << 17;
+constexpr size_t kScratchDescs = 256;                                                   // after the job counter
+constexpr size_t kScratchTiles = kScratchDescs + sizeof(TensorDesc) * kNoallocMaxTensors;
+constexpr size_t kScratchBytes = kScratchTiles + sizeof(TileRef) * kNoallocMaxUnits;   // 1 122 560 bytes
+static_assert(kScratchTiles % 8 == 0 && sizeof(Sched) <= kScratchDescs, "scratch layout");
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+// device address of `scratch` per device (each GPU holds its own copy of the array)
+unsigned char* g_scratch_ptr[kMaxDevices];
+
+q8_status scratch_address(unsigned char** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return Q8_ELAUNCH;
+    std::lock_guard<std::mutex> lock(g_dev_mutex);
+    if (!g_scratch_ptr[dev]) {
+        unsigned char* ptr = nullptr;
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return Q8_ELAUNCH;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return Q8_OK;
+}
+
+// One launch carries up to kFillChunk descriptors in its arguments (under the 4 KB limit).
+constexpr int kFillChunk = 40;
+struct FillArgs {
+    TensorDesc desc[kFillChunk];
+    int32_t first_unit[kFillChunk];     // position of the tensor's first unit in the unit table
+    int32_t units[kFillChunk];
+    int32_t first_tensor, count;
+    int32_t clear_counter;              // the first chunk also zeroes the job counter
+};
+static_assert(sizeof(FillArgs) + 8 <= 3584, "kernel arguments stay well under 4 KB");
+
+// Workgroup b writes descriptor (first_tensor + b) and that tensor's rows of the unit table.
+__global__ __launch_bounds__(256) void fill_tables_kernel(FillArgs a, unsigned char* base)
+{
+    const int b = blockIdx.x;
+    if (b >= a.count) return;
+    TensorDesc* descs = reinterpret_cast<TensorDesc*>(base + kScratchDescs);
+    TileRef* tiles = reinterpret_cast<TileRef*>(base + kScratchTiles);
+    if (threadIdx.x == 0) {
+        descs[a.first_tensor + b] = a.desc[b];
+        if (a.clear_counter && b == 0) {
+            Sched* s = reinterpret_cast<Sched*>(base);
+            s->next = 0;
+            s->done = 0;
+        }
+    }
+    for (int j = threadIdx.x; j < a.units[b]; j += blockDim.x)
+        tiles[a.first_unit[b] + j] = TileRef{a.first_tensor + b, j};
+}
+
+}  // namespace
+
+extern "C" q8_status q8_multi_adam8bit_step_noalloc(const q8_tensor* list, int count, int B,
+                                                    const void* qtable_signed, const void* qtable_unsigned,
+                                                    float alpha, float beta1, float beta2, float eps,
+                                                    float weight_decay, int64_t t, int flags, void* stream)
+{
+    if (!list || count <= 0 || !qtable_signed || !qtable_unsigned) return Q8_EINVAL;
+    if (!valid_block(B)) return Q8_EBLOCK;
+    if (!aligned(qtable_signed, 16) || !aligned(qtable_unsigned, 16)) return Q8_EALIGN;
+    AdamScalars sc;
+    q8_status st = make_adam_scalars(alpha, beta1, beta2, eps, weight_decay, t, flags, sc);
+    if (st != Q8_OK) return st;
+    if (count > kNoallocMaxTensors) return Q8_ELIMIT;
+    const int64_t te = unit_elems(B);
+    int64_t nunits = 0;
+    bool has_r = true;
+    for (int i = 0; i < count; ++i) {
+        int64_t nt = 0;
+        st = check_tensor(list[i], wg_align(kStoreF32), te, nt, has_r);
+        if (st != Q8_OK) return st;
+        nunits += nt;
+        if (nunits > kNoallocMaxUnits) return Q8_ELIMIT;
+    }
+    if (!has_r) return Q8_EINVAL;
+    if (nunits == 0) return Q8_OK;
+    unsigned char* ptr = nullptr;
+    st = scratch_address(&ptr);
+    if (st != Q8_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t unit0 = 0;
+    for (int first = 0; first < count; first += kFillChunk) {
+        FillArgs fa{};
+        fa.first_tensor = first;
+        fa.count = (count - first < kFillChunk) ? count - first : kFillChunk;
+        fa.clear_counter = (first == 0) ? 1 : 0;
+        for (int k = 0; k < fa.count; ++k) {
+            const q8_tensor& x = list[first + k];
+            fa.desc[k] = TensorDesc{x.w, x.g, x.m_q, x.r_q, x.N_m, x.N_r, x.m_f32, x.r_f32, x.n};
+            fa.first_unit[k] = (int32_t)unit0;
+            fa.units[k] = (int32_t)((x.n + te - 1) / te);
+            unit0 += fa.units[k];
+        }
+        hipLaunchKernelGGL(fill_tables_kernel, dim3(fa.count), dim3(256), 0, s, fa, ptr);
+        if (launch_status() != Q8_OK) return Q8_ELAUNCH;
+    }
+    StepArgs a{};
+    a.descs = reinterpret_cast<const TensorDesc*>(ptr + kScratchDescs);
+    a.tiles = reinterpret_cast<const TileRef*>(ptr + kScratchTiles);
+    a.nunits = nunits;
+    a.qtab_s = qtable_signed;
+    a.qtab_u = qtable_unsigned;
+    a.sched = reinterpret_cast<Sched*>(ptr);
+    return run_adam(kStoreF32, B, a, sc, s);
 }

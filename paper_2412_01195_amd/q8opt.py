@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libq8opt.so")
 FLAG_BIAS_CORRECTION = 1
 FLAG_DECOUPLED_WD = 2
 
-OK, EINVAL, EALIGN, EBLOCK, ELAUNCH, ENOMEM, ECODEBOOK = 0, -1, -2, -3, -4, -5, -6
+OK, EINVAL, EALIGN, EBLOCK, ELAUNCH, ENOMEM, ECODEBOOK, ELIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 
 EXPORTS = (
     "q8_status_str", "q8_build_codebook", "q8_qtable_bytes", "q8_build_qtable", "q8_host_nearest_code",
@@ -27,6 +27,7 @@ EXPORTS = (
     "q8_plan_create", "q8_plan_destroy", "q8_multi_adam8bit_step", "q8_multi_sgd8bit_step",
     "q8_adam8bit_step_bf16", "q8_sgd8bit_step_bf16", "q8_plan_create_bf16",
     "q8_adam8bit_step_f16", "q8_sgd8bit_step_f16", "q8_plan_create_f16",
+    "q8_multi_adam8bit_step_noalloc",
 )
 
 
@@ -72,6 +73,8 @@ def lib():
         L.q8_plan_destroy.argtypes = [vp]
         L.q8_multi_adam8bit_step.argtypes = [vp, vp, vp, f32, f32, f32, f32, f32, i64, i32, vp]
         L.q8_multi_sgd8bit_step.argtypes = [vp, vp, f32, f32, f32, vp]
+        L.q8_multi_adam8bit_step_noalloc.argtypes = [C.POINTER(q8_tensor), i32, i32, vp, vp,
+                                                     f32, f32, f32, f32, f32, i64, i32, vp]
         for name in EXPORTS:
             if name not in ("q8_status_str", "q8_qtable_bytes"):
                 getattr(L, name).restype = i32
@@ -205,6 +208,27 @@ def sgd8bit_step_f16(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight_
     _sgd("q8_sgd8bit_step_f16", "float16", w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n)
 
 
+def _tensor_array(tensors: Sequence[dict], wg: str):
+    arr = (q8_tensor * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i].w = _ptr(t["w"], wg); arr[i].g = _ptr(t["g"], wg); arr[i].n = t["w"].numel()
+        arr[i].m_q = _ptr(t.get("m_q"), "uint8"); arr[i].r_q = _ptr(t.get("r_q"), "uint8")
+        arr[i].N_m = _ptr(t.get("N_m"), "float32"); arr[i].N_r = _ptr(t.get("N_r"), "float32")
+        arr[i].m_f32 = _ptr(t.get("m_f32"), "float32"); arr[i].r_f32 = _ptr(t.get("r_f32"), "float32")
+    return arr
+
+
+def multi_adam8bit_step_noalloc(tensors: Sequence[dict], B: int, qtable_signed, qtable_unsigned,
+                                alpha, beta1, beta2, eps, weight_decay=0.0, t=1, flags=0):
+    """q8_multi_adam8bit_step_noalloc: one Adam step over a list of fp32 tensors (dicts as for Plan)
+    without a plan and without any device allocation by the library."""
+    arr = _tensor_array(tensors, "float32")
+    _check(lib().q8_multi_adam8bit_step_noalloc(arr, len(tensors), B, _ptr(qtable_signed, "uint8"),
+                                                _ptr(qtable_unsigned, "uint8"), alpha, beta1, beta2, eps,
+                                                weight_decay, t, flags, _stream()),
+           "q8_multi_adam8bit_step_noalloc")
+
+
 class Plan:
     """q8_plan: a list of parameter tensors updated by one launch.
 
@@ -213,16 +237,11 @@ class Plan:
     (q8_plan_create, q8_plan_create_bf16, q8_plan_create_f16); bf16=True is short for "bfloat16"."""
 
     def __init__(self, tensors: Sequence[dict], B: int, bf16: bool = False, wg_dtype: Optional[str] = None):
-        arr = (q8_tensor * len(tensors))()
         self._keep = list(tensors)
         wg = wg_dtype or ("bfloat16" if bf16 else "float32")
         if wg not in ("float32", "bfloat16", "float16"):
             raise ValueError("wg_dtype must be float32, bfloat16 or float16")
-        for i, t in enumerate(tensors):
-            arr[i].w = _ptr(t["w"], wg); arr[i].g = _ptr(t["g"], wg); arr[i].n = t["w"].numel()
-            arr[i].m_q = _ptr(t.get("m_q"), "uint8"); arr[i].r_q = _ptr(t.get("r_q"), "uint8")
-            arr[i].N_m = _ptr(t.get("N_m"), "float32"); arr[i].N_r = _ptr(t.get("N_r"), "float32")
-            arr[i].m_f32 = _ptr(t.get("m_f32"), "float32"); arr[i].r_f32 = _ptr(t.get("r_f32"), "float32")
+        arr = _tensor_array(tensors, wg)
         h = C.c_void_p()
         create = {"float32": lib().q8_plan_create, "bfloat16": lib().q8_plan_create_bf16,
                   "float16": lib().q8_plan_create_f16}[wg]
