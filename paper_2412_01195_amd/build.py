@@ -18,7 +18,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libq8opt.so")
 PROBE_LIB = os.path.join(HERE, "libq8opt_probe.so")
-HEADERS = [os.path.join(CSRC, "q8opt_internal.h"), os.path.join(CSRC, "q8opt_device.h"),
+HEADERS = [os.path.join(CSRC, "q8opt_internal.h"), os.path.join(CSRC, "q8opt_device.h"), os.path.join(CSRC, "q8opt_exact.h"),
            os.path.join(ROOT, "include", "q8opt.h")]
 # (object name, source, extra defines)
 UNITS = [

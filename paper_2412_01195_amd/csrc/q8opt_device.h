@@ -49,6 +49,7 @@
 #include <atomic>
 
 #include "q8opt.h"
+#include "q8opt_exact.h"
 #include "q8opt_internal.h"
 
 namespace q8 {
@@ -230,21 +231,10 @@ __device__ __forceinline__ uint32_t group_max(uint32_t v, int lane)
     return v;
 }
 
-// Correctly rounded a / N for a block-uniform N in [2^-60, 2^60], |a| <= N, with
-// y = RN(1/N) and ylo = RN(RN(1 - N y) y), so that y + ylo = 1/N to about 2^-46.
-// q = RN(a y + RN(a ylo)) is then a faithful quotient, and one residual correction
-// with the correctly rounded reciprocal returns RN(a/N) (Markstein's division
-// theorem).  When the quotient is below the normal range (|a/N| < 2^-126) the
-// result may be off in its last bits; such values lie far below the smallest
-// threshold and get the same code.  Checked on the CPU against true division on
-// 3e9 random and near-midpoint pairs.
-__device__ __forceinline__ float div_fast(float a, float N, float y, float ylo)
-{
-    float t = a * ylo;
-    float q = __builtin_fmaf(a, y, t);
-    float r = __builtin_fmaf(-q, N, a);
-    return __builtin_fmaf(r, y, q);
-}
+using exact::div_fast;
+using exact::norm_in_fast_range;
+using exact::kFastLo;
+using exact::kFastHi;
 
 __device__ __forceinline__ float div_any(float a, float N)
 {
@@ -253,11 +243,6 @@ __device__ __forceinline__ float div_any(float a, float N)
 
 struct BlockNorm { float N, y, ylo; bool fast; };
 
-__device__ __forceinline__ bool norm_in_fast_range(uint32_t nbits)
-{
-    return (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
-}
-
 // Reciprocal data of one block maximum held per lane (used when lanes of a wave
 // belong to different blocks, B < 256).
 __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
@@ -265,9 +250,7 @@ __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
     BlockNorm b;
     b.N = __uint_as_float(nbits);
     b.fast = norm_in_fast_range(nbits);
-    b.y = b.fast ? 1.0f / b.N : 0.0f;
-    const float e = __builtin_fmaf(-b.N, b.y, 1.0f);
-    b.ylo = e * b.y;
+    exact::reciprocal_pair(b.fast ? b.N : 1.0f, b.y, b.ylo);
     return b;
 }
 
@@ -279,10 +262,8 @@ __device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm
     int v = (int)nbits[0];
 #pragma unroll
     for (int k = 1; k < K; ++k) v = (lane == k) ? (int)nbits[k] : v;
-    const float N = __int_as_float(v);
-    const float y = norm_in_fast_range((uint32_t)v) ? 1.0f / N : 0.0f;
-    const float e = __builtin_fmaf(-N, y, 1.0f);
-    const float ylo = e * y;
+    float y, ylo;
+    exact::reciprocal_pair(norm_in_fast_range((uint32_t)v) ? __int_as_float(v) : 1.0f, y, ylo);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         out[k].N = __uint_as_float(nbits[k]);
@@ -292,49 +273,17 @@ __device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm
     }
 }
 
-// Short forms of the square root and of the division in the Adam weight update,
-// used on rows where every new state lies in [kFastLo, kFastHi] (and the host has
-// found eps and the bias-correction factor within [0, 2^10] resp. [1, 2^10]); all
-// other rows take sqrtf and the general a / b.
-//
-// Square root: v_sqrt_f32 is within one ulp; the two neighbours are tested with fma
-// residuals, which are exact in this range: r - s_dn s <= 0 means sqrt(r) lies below
-// the midpoint of s_dn and s (the geometric mean of two neighbours is within a
-// quarter ulp^2 of their midpoint, closer than any binary32 r can come), likewise
-// for s_up.
-//
-// Division: for r in the range, d = fma(sqrt(r), c, eps) lies in [2^-40, 2^31] and
-// |m| / d in [2^-111, 2^80].  For such operands the compiler's correctly rounded
-// a / b -- v_div_scale, v_rcp, one reciprocal refinement, a product and two quotient
-// refinements, v_div_fmas, v_div_fixup -- scales nothing and fixes nothing up (no
-// operand or quotient is zero, subnormal or near the exponent limits, the exponents
-// differ by less than 96), so the same chain of fma without those three
-// instructions returns the same bits.
-constexpr float kFastLo = 0x1p-80f;
-constexpr float kFastHi = 0x1p40f;
-
+// Short forms of the square root and of the division in the Adam weight update (q8opt_exact.h),
+// seeded with the hardware's approximate reciprocal and square root; used on rows where every
+// new state lies in [kFastLo, kFastHi], all other rows take sqrtf and the general a / b.
 __device__ __forceinline__ float div_rn_inrange(float a, float b)
 {
-    float y = __builtin_amdgcn_rcpf(b);
-    const float e = __builtin_fmaf(-b, y, 1.0f);
-    y = __builtin_fmaf(e, y, y);
-    float q = a * y;
-    float r = __builtin_fmaf(-b, q, a);
-    q = __builtin_fmaf(r, y, q);
-    r = __builtin_fmaf(-b, q, a);
-    return __builtin_fmaf(r, y, q);
+    return exact::div_rn_from_seed(a, b, __builtin_amdgcn_rcpf(b));
 }
 
 __device__ __forceinline__ float sqrt_rn_fast(float r)
 {
-    const float s = __builtin_amdgcn_sqrtf(r);
-    const float s_dn = __uint_as_float(__float_as_uint(s) - 1u);
-    const float s_up = __uint_as_float(__float_as_uint(s) + 1u);
-    const float e_dn = __builtin_fmaf(-s_dn, s, r);
-    const float e_up = __builtin_fmaf(-s_up, s, r);
-    float out = (e_dn <= 0.0f) ? s_dn : s;
-    out = (e_up > 0.0f) ? s_up : out;
-    return out;
+    return exact::sqrt_rn_from_seed(r, __builtin_amdgcn_sqrtf(r));
 }
 
 // ---------------------------------------------------------------------------

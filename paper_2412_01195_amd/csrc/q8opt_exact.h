@@ -1,0 +1,93 @@
+// The short, exactly rounded forms of division and square root that the kernels use in place
+// of the general a / b and sqrtf.  Plain functions of binary32 values built from fma, so that
+// the very same source compiles for the GPU (inside q8opt_device.h) and for the host, where
+// tests/test_exact_devices.py checks each of them against IEEE division and square root on
+// random, adversarial and threshold-hugging operands (no GPU needed).  The hardware's
+// approximate reciprocal and square root enter as arguments ("seed"): the host check feeds
+// every binary32 value within one unit in the last place of the true result, which covers
+// whatever the instruction returns.
+#ifndef Q8OPT_EXACT_H
+#define Q8OPT_EXACT_H
+
+#include <stdint.h>
+
+#if defined(__HIP_DEVICE_COMPILE__) || defined(__HIPCC__)
+#define Q8_EXACT_FN __device__ __host__ __forceinline__
+#else
+#define Q8_EXACT_FN static inline
+#endif
+
+namespace q8 {
+namespace exact {
+
+Q8_EXACT_FN float bits_as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
+Q8_EXACT_FN uint32_t float_as_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+// ---- Normalisation x = a / N (Eq. quant1) by a block-uniform N in [2^-60, 2^60], |a| <= N.
+// Once per block: y = RN(1/N) (an IEEE division) and ylo = RN(RN(1 - N y) y), so that
+// y + ylo = 1/N to about 2^-46.
+Q8_EXACT_FN bool norm_in_fast_range(uint32_t nbits)
+{
+    return (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
+}
+
+Q8_EXACT_FN void reciprocal_pair(float N, float& y, float& ylo)
+{
+    y = 1.0f / N;
+    const float e = __builtin_fmaf(-N, y, 1.0f);
+    ylo = e * y;
+}
+
+// Per element: q = RN(a y + RN(a ylo)) is a faithful quotient, and one residual correction
+// with the correctly rounded reciprocal returns RN(a/N) (Markstein's division theorem).
+// When the quotient is below the normal range (|a/N| < 2^-126) the result may be off in its
+// last bits; such values lie far below the smallest decision threshold of any codebook the
+// table builder accepts and get the same code.
+Q8_EXACT_FN float div_fast(float a, float N, float y, float ylo)
+{
+    const float t = a * ylo;
+    const float q = __builtin_fmaf(a, y, t);
+    const float r = __builtin_fmaf(-q, N, a);
+    return __builtin_fmaf(r, y, q);
+}
+
+// ---- Weight update of Eq. adam on rows whose new states all lie in [kFastLo, kFastHi]
+// (and eps in [0, 2^10], bias-correction factor in [1, 2^10]).
+constexpr float kFastLo = 0x1p-80f;
+constexpr float kFastHi = 0x1p40f;
+
+// Division: for r in the range, d = sqrt(r) c + eps lies in [2^-40, 2^31] and |m| / d in
+// [2^-111, 2^80].  For such operands the classical correctly rounded sequence -- approximate
+// reciprocal, one reciprocal refinement, a product and two quotient refinements -- needs
+// neither operand scaling nor a final fix-up (no operand or quotient is zero, subnormal or
+// near the exponent limits).  `y0` = approximate 1/b, within one ulp.
+Q8_EXACT_FN float div_rn_from_seed(float a, float b, float y0)
+{
+    const float e = __builtin_fmaf(-b, y0, 1.0f);
+    const float y = __builtin_fmaf(e, y0, y0);
+    float q = a * y;
+    float r = __builtin_fmaf(-b, q, a);
+    q = __builtin_fmaf(r, y, q);
+    r = __builtin_fmaf(-b, q, a);
+    return __builtin_fmaf(r, y, q);
+}
+
+// Square root: `s` = approximate sqrt(r), within one ulp.  The two neighbours are tested with
+// fma residuals, which are exact in this range: r - s_dn s <= 0 means sqrt(r) lies below the
+// midpoint of s_dn and s (the geometric mean of two neighbours is within a quarter ulp^2 of
+// their midpoint, closer than any binary32 r can come), likewise for s_up.
+Q8_EXACT_FN float sqrt_rn_from_seed(float r, float s)
+{
+    const float s_dn = bits_as_float(float_as_bits(s) - 1u);
+    const float s_up = bits_as_float(float_as_bits(s) + 1u);
+    const float e_dn = __builtin_fmaf(-s_dn, s, r);
+    const float e_up = __builtin_fmaf(-s_up, s, r);
+    float out = (e_dn <= 0.0f) ? s_dn : s;
+    out = (e_up > 0.0f) ? s_up : out;
+    return out;
+}
+
+}  // namespace exact
+}  // namespace q8
+
+#endif  // Q8OPT_EXACT_H

@@ -62,7 +62,7 @@ inline uint32_t float_to_bits(float f) { uint32_t b; std::memcpy(&b, &f, 4); ret
 // number of thresholds <= x
 int count_le(const float* thr, float x)
 {
-    int lo = 0, hi = 255;                          // thr[255] = +inf is never <= x
+    int lo = 0, hi = 255;                          // thr[255] is not a threshold: never looked at
     while (lo < hi) {
         int mid = (lo + hi) / 2;
         if (thr[mid] <= x) lo = mid + 1; else hi = mid;
@@ -95,7 +95,7 @@ extern "C" q8_status q8_build_qtable(const float* qmap, void* qtable_out)
         thr[j] = f;
         if (j && !(thr[j] > thr[j - 1])) return Q8_ECODEBOOK;
     }
-    thr[255] = std::numeric_limits<float>::infinity();
+    thr[255] = std::numeric_limits<float>::quiet_NaN();      // x >= thr[255] is false for every x: code 255 is the last
 
     // Bucket table over all 65536 upper halves of a binary32 pattern.
     const int code_p1 = count_le(thr, 1.0f), code_m1 = count_le(thr, -1.0f);

@@ -8,7 +8,7 @@ namespace q8 {
 //   [0, 64)          header (QTabHeader)
 //   [64, 1088)       codebook Q^map, 256 binary32 values, ascending
 //   [1088, 2112)     thresholds: thr[j] = first binary32 above (Q_j + Q_j+1)/2 for
-//                    j < 255, thr[255] = +inf; code(x) = #{j : thr[j] <= x}
+//                    j < 255, thr[255] = NaN (no x, not even +Inf, compares >= it); code(x) = #{j : thr[j] <= x}
 //   [2112, 67648)    bucket table, one byte per bucket, indexed by the upper 16
 //                    bits of the binary32 pattern of x (sign, exponent, 7 mantissa
 //                    bits).  The entry is the code of the smallest x in the bucket;

@@ -1,0 +1,111 @@
+// Host-side check of the kernels' exactly rounded division and square-root forms: compiled by
+// tests/test_exact_devices.py from the library's own header (csrc/q8opt_exact.h), so what is
+// checked here is the source the GPU runs.  Each function returns the number of operands whose
+// result differs from the IEEE operation and stores the index of the first such operand.
+//   g++ -O2 -ffp-contract=off -mfma -shared -fPIC
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "q8opt_exact.h"
+
+using namespace q8::exact;
+
+namespace {
+inline uint32_t bits(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
+inline float next_up(float f) { return std::nextafterf(f, INFINITY); }
+inline float next_dn(float f) { return std::nextafterf(f, -INFINITY); }
+
+// splitmix64: the test's own generator for the random sweeps
+inline uint64_t mix(uint64_t& s)
+{
+    uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+}  // namespace
+
+extern "C" {
+
+// Normalisation: a[i] / N[i] with |a| <= N, N in [2^-60, 2^60].  A quotient in the normal
+// range must equal the IEEE quotient bit for bit; below it, both must stay below 2^-100 in
+// magnitude with the same sign (far under any threshold: same code).
+int64_t check_div_fast_pairs(const float* a, const float* N, int64_t n, int64_t* first_bad)
+{
+    int64_t bad = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (!norm_in_fast_range(bits(N[i])) || !(std::fabs(a[i]) <= N[i])) { if (!bad++) *first_bad = i; continue; }
+        float y, ylo;
+        reciprocal_pair(N[i], y, ylo);
+        const float got = div_fast(a[i], N[i], y, ylo), want = a[i] / N[i];
+        bool ok;
+        if (std::fabs(want) >= 0x1p-126f) ok = bits(got) == bits(want);
+        else ok = std::fabs(got) < 0x1p-100f && (got == 0.0f || want == 0.0f || std::signbit(got) == std::signbit(want));
+        if (!ok && !bad++) *first_bad = i;
+    }
+    return bad;
+}
+
+// Random sweep: N = 2^e * m with e in [-60, 59], a = N * u for u spread over [-1, 1] on a
+// logarithmic scale down to 2^-40, plus a = N and a = -N.
+int64_t check_div_fast_random(uint64_t seed, int64_t count, float* bad_a, float* bad_N)
+{
+    int64_t bad = 0;
+    uint64_t s = seed;
+    for (int64_t i = 0; i < count; ++i) {
+        const uint64_t r1 = mix(s), r2 = mix(s);
+        const int e = (int)(r1 % 120) - 60;
+        const float N = std::ldexp(1.0f + (float)((r1 >> 20) & 0x7fffff) / 8388608.0f, e);
+        const int eu = -(int)((r2 >> 8) % 41);
+        float a = N * std::ldexp((float)((r2 >> 20) & 0xffffff) / 16777216.0f, eu);
+        if (r2 & 1) a = -a;
+        if ((r2 & 0xfe) == 0) a = (r2 & 1) ? -N : N;
+        if (!(std::fabs(a) <= N) || !norm_in_fast_range(bits(N))) continue;
+        float y, ylo;
+        reciprocal_pair(N, y, ylo);
+        const float got = div_fast(a, N, y, ylo), want = a / N;
+        const bool ok = (std::fabs(want) >= 0x1p-126f) ? bits(got) == bits(want) : std::fabs(got) < 0x1p-100f;
+        if (!ok && !bad++) { *bad_a = a; *bad_N = N; }
+    }
+    return bad;
+}
+
+// A seed is admissible if it lies within one unit in the last place of the TRUE value (the
+// accuracy the instruction set documents for the approximate reciprocal and square root).
+inline bool admissible(float seed, double truth)
+{
+    const double ulp = (double)next_up(std::fabs(seed)) - (double)std::fabs(seed);
+    return std::fabs((double)seed - truth) <= ulp;
+}
+
+// Weight-update division m / d with every admissible seed for 1/d.
+int64_t check_div_seeds(const float* m, const float* d, int64_t n, int64_t* first_bad)
+{
+    int64_t bad = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const float want = m[i] / d[i];
+        const float y = 1.0f / d[i];
+        const float seeds[3] = {next_dn(y), y, next_up(y)};
+        for (float y0 : seeds)
+            if (admissible(y0, 1.0 / (double)d[i]) && bits(div_rn_from_seed(m[i], d[i], y0)) != bits(want) && !bad++)
+                *first_bad = i;
+    }
+    return bad;
+}
+
+// Square root with every admissible seed for sqrt(r).
+int64_t check_sqrt_seeds(const float* r, int64_t n, int64_t* first_bad)
+{
+    int64_t bad = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const float want = std::sqrt(r[i]);
+        const float seeds[3] = {next_dn(want), want, next_up(want)};
+        for (float s0 : seeds)
+            if (admissible(s0, std::sqrt((double)r[i])) && bits(sqrt_rn_from_seed(r[i], s0)) != bits(want) && !bad++)
+                *first_bad = i;
+    }
+    return bad;
+}
+
+}  // extern "C"
