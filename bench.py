@@ -36,6 +36,8 @@ WORKLOADS = {
     "bf16_1b": dict(n=1_000_000_000, B=2048, name="flat bfloat16 weights and gradients (extension), 1e9 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "f16_1b": dict(n=1_000_000_000, B=2048, name="flat binary16 weights and gradients (extension), 1e9 params, 8-bit Adam, B=2048, grads N(0,1e-3)"),
     "sgd1b": dict(n=1_000_000_000, B=2048, name="flat fp32 tensor, 1e9 params, 8-bit SGD momentum, B=2048, grads N(0,1e-3)"),
+    "probe1b": dict(n=1_000_000_000, B=2048, name="traffic of the config-4 step without its arithmetic (measurement aid): read w, g, both "
+                    "code arrays, write w and both code arrays back unchanged; 1e9 params"),
 }
 
 
@@ -163,13 +165,12 @@ def build_workload(name, torch, q8opt, dev):
             q8opt.sgd8bit_step(w, g, st["m_q"], st["N_m"], tab_s, B, 0.1, 0.9, 1e-4)
         return wl["name"], n, 14 * n + 8 * (-(-n // B)), "sgd8_kernel<%d, float>" % B, step, None, keep
     if name == "probe1b":
-        n = 1_000_000_000
+        n = WORKLOADS[name]["n"]
         w = torch.empty(n, device=dev).uniform_(-0.1, 0.1, generator=gen)
         g = torch.empty(n, device=dev).normal_(0.0, 1e-3, generator=gen)
         st = state8(n, 2048, True)
         probe = load_traffic_probe()
-        return ("traffic of the config-4 step without its arithmetic (measurement aid): read w, g, both code arrays, "
-                "write w and both code arrays back unchanged; 1e9 params", n, 16 * n, "traffic_probe_kernel",
+        return (WORKLOADS[name]["name"], n, 16 * n, "traffic_probe_kernel",
                 lambda: probe(w, g, st["m_q"], st["r_q"], tab_s, tab_u), None, keep)
     if name in ("quant1b", "dequant1b"):
         n, B = 1_000_000_000, 2048

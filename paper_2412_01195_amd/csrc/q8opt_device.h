@@ -135,14 +135,15 @@ typedef Q8_GLOBAL const v2u gcv2u;
 
 
 // ---------------------------------------------------------------------------
-// LDS map (64 KB per workgroup).  The bucket table is indexed by the upper half
-// of a binary32 pattern: keys of x in [0, 1] are 0 .. 0x3F80 and keys of x in
-// [-1, -0] are 0x8000 .. 0xBF80, which leaves two holes.  The first hole hosts
-// the non-negative half of the second table (used for the state r >= 0), the
-// second one the two codebooks and threshold arrays.  Every 16-bit key, also
-// that of a NaN, stays inside the 64 KB.
+// LDS map (52 KB per workgroup, so that three workgroups fit a CU's 160 KB).  The bucket
+// table is indexed by the upper half of a binary32 pattern: keys of x in [0, 1] are
+// 0 .. 0x3F80 and keys of x in [-1, -0] are 0x8000 .. 0xBF80, which leaves two holes.  The
+// first hole hosts the non-negative half of the second table (used for the state r >= 0),
+// the space above the negative keys the two codebooks and threshold arrays.  Finite inputs
+// give |x| <= 1 and stay inside the staged ranges; any other bit pattern (NaN, Inf) is
+// clamped to the last byte of the map, so that every access stays inside the 52 KB.
 // ---------------------------------------------------------------------------
-constexpr int kLdsBytes = 0x10000;
+constexpr int kLdsBytes = 0xD000;
 constexpr int kLutHalf = 0x3F90;          // bytes staged per half: keys 0 .. 0x3F8F
 constexpr int kLdsNeg = 0x8000;           // keys of negative x
 constexpr int kLdsU = 0x3F90;             // second table, keys of x >= 0
@@ -150,7 +151,9 @@ constexpr int kLdsQ1 = 0xC000;            // first table: codebook, then thresho
 constexpr int kLdsT1 = 0xC400;
 constexpr int kLdsQ2 = 0xC800;            // second table
 constexpr int kLdsT2 = 0xCC00;
+constexpr uint32_t kLdsLastKey = kLdsBytes - 1;
 static_assert(kLdsU + kLutHalf <= kLdsNeg && kLdsNeg + kLutHalf <= kLdsQ1 && kLdsT2 + 1024 <= kLdsBytes, "LDS map");
+static_assert(kLdsU + 0x7fff < kLdsBytes, "every 15-bit key of the second table stays inside the map");
 
 __device__ __forceinline__ void copy16(unsigned char* dst, const unsigned char* src, int bytes, int tid)
 {
@@ -188,7 +191,8 @@ __device__ __forceinline__ uint32_t nearest_code(const unsigned char* lds, float
         c = lds[kLdsU + __builtin_amdgcn_ubfe(bits, 16, 15)];
         t = *reinterpret_cast<const float*>(lds + kLdsT2 + 4 * c);
     } else {
-        c = lds[bits >> 16];
+        const uint32_t key = bits >> 16;
+        c = lds[key < kLdsLastKey ? key : kLdsLastKey];
         t = *reinterpret_cast<const float*>(lds + kLdsT1 + 4 * c);
     }
     return c + ((x >= t) ? 1u : 0u);
@@ -365,6 +369,16 @@ template <> struct Wide<float> { typedef gfloat* ptr; typedef gcfloat* cptr; };
 template <> struct Wide<Bf16> { typedef gu16* ptr; typedef gcu16* cptr; };
 template <> struct Wide<F16> { typedef gu16* ptr; typedef gcu16* cptr; };
 
+// Workgroups per CU the step kernels are built and launched for.  With binary32 weights and
+// gradients the step is bound by its memory access pattern and two workgroups per CU (16
+// waves, up to 128 VGPRs) measured best; with 16-bit storage it moves 10 instead of 16 bytes
+// per parameter and is bound by instruction issue: three workgroups per CU (24 waves, 80
+// VGPRs, the 52 KB LDS map fits three times) measured 6 % faster there and 3 % slower with
+// binary32 storage.
+template <typename WT> struct Occupancy { static constexpr int kWgPerCu = 2; };
+template <> struct Occupancy<Bf16> { static constexpr int kWgPerCu = 3; };
+template <> struct Occupancy<F16> { static constexpr int kWgPerCu = 3; };
+
 template <typename WT> __device__ __forceinline__ void widen2(uint32_t pair, float& lo, float& hi);
 template <> __device__ __forceinline__ void widen2<Bf16>(uint32_t pair, float& lo, float& hi)
 {
@@ -390,28 +404,54 @@ template <> __device__ __forceinline__ uint32_t narrow2<F16>(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(x, v2h));
 }
 
+// Four loaded elements as they sit in registers until they are used: binary32 values as
+// they are, 16-bit values still packed in pairs (widened only where the arithmetic starts,
+// which keeps a tile's loads in half the registers).
+template <typename WT> struct Raw4 { uint32_t a, b; };
+template <> struct Raw4<float> { float v[4]; };
+
 template <typename WT>
-__device__ __forceinline__ void load4w(gcfloat* p, int cnt, float (&v)[4]) { load4f(p, cnt, v); }
+__device__ __forceinline__ void load4raw(gcfloat* p, int cnt, Raw4<float>& out) { load4f(p, cnt, out.v); }
 template <typename WT>
 __device__ __forceinline__ void store4w(gfloat* p, int cnt, const float (&v)[4]) { store4f(p, cnt, v); }
 
 template <typename WT>
-__device__ __forceinline__ void load4w(gcu16* p, int cnt, float (&v)[4])
+__device__ __forceinline__ void load4raw(gcu16* p, int cnt, Raw4<WT>& out)
 {
-    uint32_t a, b;
     if (cnt == 4) {
         const v2u t = __builtin_nontemporal_load((gcv2u*)p);
-        a = t.x;
-        b = t.y;
+        out.a = t.x;
+        out.b = t.y;
     } else {
         uint32_t h[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) h[j] = (j < cnt) ? (uint32_t)p[j] : 0u;
-        a = h[0] | (h[1] << 16);
-        b = h[2] | (h[3] << 16);
+        out.a = h[0] | (h[1] << 16);
+        out.b = h[2] | (h[3] << 16);
     }
-    widen2<WT>(a, v[0], v[1]);
-    widen2<WT>(b, v[2], v[3]);
+}
+
+__device__ __forceinline__ void zero4raw(Raw4<float>& x) { x.v[0] = x.v[1] = x.v[2] = x.v[3] = 0.0f; }
+template <typename WT> __device__ __forceinline__ void zero4raw(Raw4<WT>& x) { x.a = 0; x.b = 0; }
+
+__device__ __forceinline__ void widen4(const Raw4<float>& x, float (&v)[4])
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) v[j] = x.v[j];
+}
+template <typename WT>
+__device__ __forceinline__ void widen4(const Raw4<WT>& x, float (&v)[4])
+{
+    widen2<WT>(x.a, v[0], v[1]);
+    widen2<WT>(x.b, v[2], v[3]);
+}
+
+template <typename WT, typename P>
+__device__ __forceinline__ void load4w(P p, int cnt, float (&v)[4])
+{
+    Raw4<WT> raw;
+    load4raw<WT>(p, cnt, raw);
+    widen4(raw, v);
 }
 
 template <typename WT>
@@ -474,20 +514,78 @@ __device__ __forceinline__ void norms_of(const uint32_t (&nbits)[NSTATE][Shape<B
 // LDS words for the exchange of wave maxima: [parity][state][wave].
 struct Exchange { uint32_t part[2][2][kWavesPerWg]; };
 
-// Lane maxima -> wave-level block maxima (DPP reduction inside the wave).
+// Wave-wide maxima of K = 1, 2, 4 or 8 values per lane at once ("transpose and reduce"): a
+// step over lane bit 32, 16 or 8 exchanges one value of each pair with the partner lane and
+// keeps the maximum of the other, halving the number of values a lane carries; the last
+// value goes through the remaining butterfly steps.  Returns, in every lane, ONE result:
+// lane l holds the wave-wide maximum of value number l / (64 / K).
+__device__ __forceinline__ uint32_t umax(uint32_t a, uint32_t b) { return a > b ? a : b; }
+
+template <int K>
+__device__ __forceinline__ uint32_t wave_max_many(const uint32_t (&v)[K], int lane)
+{
+    static_assert(K == 1 || K == 2 || K == 4 || K == 8, "K");
+    constexpr int K1 = (K >= 2) ? K / 2 : 1;      // values per lane after the step over lane bit 32
+    constexpr int K2 = (K1 >= 2) ? K1 / 2 : 1;    // ... after lane bit 16
+    uint32_t a[K1], b[K2];
+    // lane bit 32: the lower half of the wave keeps v[i], the upper half v[i + K/2]
+#pragma unroll
+    for (int i = 0; i < K1; ++i) {
+        const auto s = __builtin_amdgcn_permlane32_swap(v[i], v[(K >= 2) ? i + K1 : i], false, false);
+        a[i] = umax(s[0], s[1]);
+    }
+    // lane bit 16
+#pragma unroll
+    for (int i = 0; i < K2; ++i) {
+        const auto s = __builtin_amdgcn_permlane16_swap(a[i], a[(K1 >= 2) ? i + K2 : i], false, false);
+        b[i] = umax(s[0], s[1]);
+    }
+    // lane bit 8: rotate each row of 16 lanes by 8
+    uint32_t x;
+    if constexpr (K2 >= 2) {
+        const bool up = (lane & 8) != 0;
+        const uint32_t keep = up ? b[1] : b[0], send = up ? b[0] : b[1];
+        x = umax(keep, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)send, 0x128, 0xf, 0xf, true));
+    } else {
+        x = dpp_max_step<0x128>(b[0]);
+    }
+    x = dpp_max_step<0x141>(x);           // row_half_mirror: lanes l and 7 - l of each 8
+    x = dpp_max_step<0x4E>(x);            // quad_perm [2,3,0,1]
+    x = dpp_max_step<0xB1>(x);            // quad_perm [1,0,3,2]
+    return x;
+}
+
+// Lane maxima -> wave-level block maxima.  Blocks that span the whole wave (B >= 256: GROUP
+// == 64) reduce all their NSTATE x NBLK values at once and read each result back from the lane
+// that holds it; smaller blocks reduce value by value inside their groups of lanes.
 template <int B, int NSTATE>
 __device__ __forceinline__ void reduce_in_wave(uint32_t (&v)[NSTATE][Shape<B>::NBLK], int lane)
 {
     using S = Shape<B>;
+    if (S::GROUP == 64) {
+        constexpr int K = NSTATE * S::NBLK;
+        uint32_t flat[K];
 #pragma unroll
-    for (int st = 0; st < NSTATE; ++st)
+        for (int st = 0; st < NSTATE; ++st)
 #pragma unroll
-        for (int k = 0; k < S::NBLK; ++k) v[st][k] = group_max<S::GROUP>(v[st][k], lane);
+            for (int k = 0; k < S::NBLK; ++k) flat[st * S::NBLK + k] = v[st][k];
+        const uint32_t x = wave_max_many<K>(flat, lane);
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k)
+                v[st][k] = (uint32_t)__builtin_amdgcn_readlane((int)x, (64 / K) * (st * S::NBLK + k));
+    } else {
+#pragma unroll
+        for (int st = 0; st < NSTATE; ++st)
+#pragma unroll
+            for (int k = 0; k < S::NBLK; ++k) v[st][k] = group_max<S::GROUP>(v[st][k], lane);
+    }
 }
 
 // When a block spans WPB > 1 waves, their maxima meet in LDS.  Every wave of the
 // workgroup calls this exactly once per job, with or without a tile (`have`; the
-// waves of one unit agree on it); it holds the one barrier of the exchange.
+// waves of one unit agree on it); it holds the one barrier between the two phases.
 // `parity` alternates between jobs so that one barrier per job suffices: a slot is
 // rewritten two jobs later, after barriers that every reader has passed.
 template <int B, int NSTATE>
@@ -495,12 +593,15 @@ __device__ __forceinline__ void exchange_block_max(uint32_t (&v)[NSTATE][Shape<B
                                                    int parity, int wave, int lane)
 {
     using S = Shape<B>;
-    if (S::WPB > 1) {
-        if (have && lane == 0) {
+    if (S::WPB > 1 && have && lane == 0) {
 #pragma unroll
-            for (int st = 0; st < NSTATE; ++st) ex->part[parity][st][wave] = v[st][0];
-        }
-        __syncthreads();
+        for (int st = 0; st < NSTATE; ++st) ex->part[parity][st][wave] = v[st][0];
+    }
+    // Blocks inside one wave (WPB == 1) have nothing to exchange, but the barrier stays: waves of
+    // a workgroup that enter the store phase of their neighbouring tiles together measured
+    // 2.5-3 % faster on 10^9 parameters (B <= 1024) than waves that drift apart.
+    __syncthreads();
+    if (S::WPB > 1) {
         if (have) {
             const int g0 = wave & ~(S::WPB - 1);
 #pragma unroll
@@ -524,13 +625,19 @@ __device__ __forceinline__ void requantize_store(const unsigned char* lds, float
                                                  int64_t n, int64_t base, int part, int lane)
 {
     using S = Shape<B>;
+    if (B >= kRow) {
+        // the maxima of the tile's block slots are neighbours in memory: lane s stores slot s
+        float mine = norms[0].N;
+#pragma unroll
+        for (int s = 1; s < S::NBLK; ++s) mine = (lane == s) ? norms[s].N : mine;
+        const int64_t row0 = base + (int64_t)lane * S::RPB * kRow;
+        if (part == 0 && lane < S::NBLK && (FULL || row0 < n)) Nout[row0 / B] = mine;
+    }
 #pragma unroll
     for (int s = 0; s < S::NBLK; ++s) {
         const BlockNorm bn = norms[s];
         const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
-        if (B >= kRow) {
-            if (part == 0 && lane == 0 && (FULL || row0 < n)) Nout[row0 / B] = bn.N;
-        } else {
+        if (B < kRow) {
             const int64_t e0 = row0 + lane * 4;
             if ((lane % S::GROUP) == 0 && (FULL || e0 < n)) Nout[e0 / B] = bn.N;
         }
@@ -573,15 +680,17 @@ __device__ __forceinline__ void load_block_maxima(const float* N, int64_t n, int
 {
     using S = Shape<B>;
     gcfloat* Ng = (gcfloat*)N;
+    if (B >= kRow) {
+        // one load for all slots: lane l reads the maximum of slot l % NBLK (neighbours in memory)
+        const int64_t row0 = base + (int64_t)(lane % S::NBLK) * S::RPB * kRow;
+        float v = 0.0f;
+        if (FULL || row0 < n) v = Ng[row0 / B];
 #pragma unroll
-    for (int s = 0; s < S::NBLK; ++s) {
-        const int64_t row0 = base + (int64_t)s * S::RPB * kRow;
-        if (B >= kRow) {
-            float v = 0.0f;
-            if (FULL || row0 < n) v = Ng[row0 / B];
-            out[s] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
-        } else {
-            const int64_t e0 = row0 + lane * 4;
+        for (int s = 0; s < S::NBLK; ++s) out[s] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), s));
+    } else {
+#pragma unroll
+        for (int s = 0; s < S::NBLK; ++s) {
+            const int64_t e0 = base + (int64_t)s * S::RPB * kRow + lane * 4;
             out[s] = (FULL || e0 < n) ? Ng[e0 / B] : 0.0f;
         }
     }
@@ -682,7 +791,7 @@ __device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, 
     typename Wide<WT>::cptr g = (typename Wide<WT>::cptr)d.g;
     gcbyte* m_q = (gcbyte*)d.m_q;
     gcbyte* r_q = (gcbyte*)d.r_q;
-    float wv[kWaveRows][4], gv[kWaveRows][4];
+    Raw4<WT> wraw[kWaveRows], graw[kWaveRows];
     uint32_t mq[kWaveRows], rq[kWaveRows];
     float Nm_old[S::NBLK], Nr_old[S::NBLK];
 #pragma unroll
@@ -690,13 +799,13 @@ __device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, 
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         if (FULL || cnt > 0) {
-            load4w<WT>(w + e0, cnt, wv[r]);
-            load4w<WT>(g + e0, cnt, gv[r]);
+            load4raw<WT>(w + e0, cnt, wraw[r]);
+            load4raw<WT>(g + e0, cnt, graw[r]);
             mq[r] = load4b(m_q + e0, cnt);
             rq[r] = load4b(r_q + e0, cnt);
         } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) { wv[r][j] = 0.0f; gv[r][j] = 0.0f; }
+            zero4raw(wraw[r]);
+            zero4raw(graw[r]);
             mq[r] = 0; rq[r] = 0;
         }
     }
@@ -709,12 +818,14 @@ __device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, 
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         const int slot = r / S::RPB;
-        float mnew[4], rnew[4];
+        float wv[4], gv[4], mnew[4], rnew[4];
+        widen4(wraw[r], wv);
+        widen4(graw[r], gv);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[slot]);
             const float r_prev = dequant<true>(lds, (rq[r] >> (8 * j)) & 0xff, Nr_old[slot]);
-            adam_states<WD>(sc, wv[r][j], gv[r][j], m_prev, r_prev, mnew[j], rnew[j]);
+            adam_states<WD>(sc, wv[j], gv[j], m_prev, r_prev, mnew[j], rnew[j]);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -732,12 +843,12 @@ __device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, 
         const bool general = !(lo >= kFastLo) || !(hi <= kFastHi) || !sc.fast_ok;
         if (__builtin_amdgcn_ballot_w64(general) == 0) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, BIAS, true>(sc, wv[r][j], mnew[j], rnew[j]);
+            for (int j = 0; j < 4; ++j) wv[j] = adam_weight<WD, BIAS, true>(sc, wv[j], mnew[j], rnew[j]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[r][j] = adam_weight<WD, BIAS, false>(sc, wv[r][j], mnew[j], rnew[j]);
+            for (int j = 0; j < 4; ++j) wv[j] = adam_weight<WD, BIAS, false>(sc, wv[j], mnew[j], rnew[j]);
         }
-        if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv[r]);
+        if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             c.val[0][r][j] = mnew[j];
@@ -918,7 +1029,10 @@ struct JobBox { long long job[2]; };
 template <int SPAN>
 __device__ __forceinline__ long long draw(Sched* sched, int round)
 {
-    if (sched) return (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
+    // the first draw of every workgroup is its own index (no atomic: the whole grid starts at
+    // once and would queue up on the one counter); the counter hands out what follows
+    if (sched && round > 0)
+        return (long long)gridDim.x * SPAN + (long long)atomicAdd(&sched->next, (unsigned long long)SPAN);
     return ((long long)blockIdx.x + (long long)round * gridDim.x) * SPAN;
 }
 
@@ -1048,7 +1162,7 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
 }
 
 template <int B, typename WT>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void adam8_kernel(StepArgs a, AdamScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256 && Occupancy<WT>::kWgPerCu == 2) ? 2 : 2 * Occupancy<WT>::kWgPerCu)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<kStepSpan>(a.sched, &lds.box);
@@ -1110,7 +1224,7 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
 }
 
 template <int B, typename WT>
-__global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void sgd8_kernel(StepArgs a, SgdScalars sc)
+__global__ __launch_bounds__(kWgThreads, ((B < 256 && Occupancy<WT>::kWgPerCu == 2) ? 2 : 2 * Occupancy<WT>::kWgPerCu)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<kStepSpan>(a.sched, &lds.box);
@@ -1172,7 +1286,8 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void 
 // `*slot` != nullptr on entry: the caller brings its own counter; otherwise one is acquired
 // for `stream` (possibly none: fixed order).
 template <typename K>
-q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, hipStream_t stream, int& grid, Sched** slot)
+q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, hipStream_t stream, int& grid, Sched** slot,
+                   int wg_per_cu_cap = 2)
 {
     int cus = 0;
     q8_status st = device_cus(cus);
@@ -1183,6 +1298,7 @@ q8_status grid_for(K kernel, std::atomic<int>& per_cu, int64_t njobs, hipStream_
             return Q8_ELAUNCH;
         per_cu.store(occ, std::memory_order_relaxed);
     }
+    if (occ > wg_per_cu_cap) occ = wg_per_cu_cap;
     int64_t want = njobs;
     int64_t cap = (int64_t)cus * occ;
     grid = (int)(want < cap ? want : cap);
@@ -1212,7 +1328,8 @@ q8_status launch_adam(StepArgs a, const AdamScalars& sc, hipStream_t stream)
 {
     static std::atomic<int> per_cu{0};
     int grid;
-    q8_status st = grid_for(adam8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &a.sched);
+    q8_status st = grid_for(adam8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &a.sched,
+                            Occupancy<WT>::kWgPerCu);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL((adam8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
@@ -1223,7 +1340,8 @@ q8_status launch_sgd(StepArgs a, const SgdScalars& sc, hipStream_t stream)
 {
     static std::atomic<int> per_cu{0};
     int grid;
-    q8_status st = grid_for(sgd8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &a.sched);
+    q8_status st = grid_for(sgd8_kernel<B, WT>, per_cu, (a.nunits + Shape<B>::UPJ - 1) / Shape<B>::UPJ, stream, grid, &a.sched,
+                            Occupancy<WT>::kWgPerCu);
     if (st != Q8_OK) return st;
     hipLaunchKernelGGL((sgd8_kernel<B, WT>), dim3(grid), dim3(kWgThreads), 0, stream, a, sc);
     return launch_status();
