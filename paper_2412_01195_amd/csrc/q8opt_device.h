@@ -813,14 +813,18 @@ __device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, 
     load_block_maxima<B, FULL>(d.N_r, n, base, lane, Nr_old);
 #pragma unroll
     for (int s = 0; s < S::NBLK; ++s) { c.amax[0][s] = 0; c.amax[1][s] = 0; }
+    // new states of all rows; `lo` collects the smallest |m| and r of the tile
+    float lo = kFastHi;
 #pragma unroll
     for (int r = 0; r < kWaveRows; ++r) {
         const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
         const int cnt = FULL ? 4 : lane_count(n, e0);
         const int slot = r / S::RPB;
-        float wv[4], gv[4], mnew[4], rnew[4];
+        float wv[4], gv[4];
         widen4(wraw[r], wv);
         widen4(graw[r], gv);
+        float (&mnew)[4] = c.val[0][r];
+        float (&rnew)[4] = c.val[1][r];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float m_prev = dequant<false>(lds, (mq[r] >> (8 * j)) & 0xff, Nm_old[slot]);
@@ -832,28 +836,34 @@ __device__ __forceinline__ void adam8_update(const TensorDesc& d, int64_t base, 
             if (!FULL && j >= cnt) { mnew[j] = 0.0f; rnew[j] = 0.0f; }
         c.amax[0][slot] = absmax4(c.amax[0][slot], mnew);
         c.amax[1][slot] = absmax4(c.amax[1][slot], rnew);
-        // one wave-uniform test per row: every |m| and r of the row within [kFastLo, kFastHi]
-        // (the running maxima bound the row from above; a row that holds an exact zero,
-        // e.g. in a ragged tail, takes the general forms)
-        float lo = __builtin_fminf(__builtin_fminf(__builtin_fabsf(mnew[0]), __builtin_fabsf(mnew[1])), __builtin_fabsf(mnew[2]));
-        lo = __builtin_fminf(__builtin_fminf(lo, __builtin_fabsf(mnew[3])), rnew[0]);
-        lo = __builtin_fminf(__builtin_fminf(lo, rnew[1]), rnew[2]);
-        lo = __builtin_fminf(lo, rnew[3]);
-        const float hi = __builtin_fmaxf(__uint_as_float(c.amax[0][slot]), __uint_as_float(c.amax[1][slot]));
-        const bool general = !(lo >= kFastLo) || !(hi <= kFastHi) || !sc.fast_ok;
-        if (__builtin_amdgcn_ballot_w64(general) == 0) {
+        lo = __builtin_fminf(__builtin_fminf(lo, __builtin_fabsf(mnew[0])), __builtin_fabsf(mnew[1]));
+        lo = __builtin_fminf(__builtin_fminf(lo, __builtin_fabsf(mnew[2])), __builtin_fabsf(mnew[3]));
+        lo = __builtin_fminf(__builtin_fminf(lo, rnew[0]), rnew[1]);
+        lo = __builtin_fminf(__builtin_fminf(lo, rnew[2]), rnew[3]);
+    }
+    // One wave-uniform test per tile: every |m| and r within [kFastLo, kFastHi] (the lane maxima
+    // bound them from above).  A tile that holds an exact zero, e.g. a ragged one, or values
+    // outside the range takes the general square root and division.
+    float hi = 0.0f;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[j] = adam_weight<WD, BIAS, true>(sc, wv[j], mnew[j], rnew[j]);
+    for (int s = 0; s < S::NBLK; ++s)
+        hi = __builtin_fmaxf(__builtin_fmaxf(hi, __uint_as_float(c.amax[0][s])), __uint_as_float(c.amax[1][s]));
+    const bool general = !(lo >= kFastLo) || !(hi <= kFastHi) || !sc.fast_ok;
+    const bool fast = __builtin_amdgcn_ballot_w64(general) == 0;
+#pragma unroll
+    for (int r = 0; r < kWaveRows; ++r) {
+        const int64_t e0 = base + (int64_t)r * kRow + lane * 4;
+        const int cnt = FULL ? 4 : lane_count(n, e0);
+        float wv[4];
+        widen4(wraw[r], wv);
+        if (fast) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) wv[j] = adam_weight<WD, BIAS, true>(sc, wv[j], c.val[0][r][j], c.val[1][r][j]);
         } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) wv[j] = adam_weight<WD, BIAS, false>(sc, wv[j], mnew[j], rnew[j]);
+            for (int j = 0; j < 4; ++j) wv[j] = adam_weight<WD, BIAS, false>(sc, wv[j], c.val[0][r][j], c.val[1][r][j]);
         }
         if (FULL || cnt > 0) store4w<WT>(w + e0, cnt, wv);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            c.val[0][r][j] = mnew[j];
-            c.val[1][r][j] = rnew[j];
-        }
     }
     reduce_in_wave<B, 2>(c.amax, lane);
 }
