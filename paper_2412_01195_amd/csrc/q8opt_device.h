@@ -369,15 +369,15 @@ template <> struct Wide<float> { typedef gfloat* ptr; typedef gcfloat* cptr; };
 template <> struct Wide<Bf16> { typedef gu16* ptr; typedef gcu16* cptr; };
 template <> struct Wide<F16> { typedef gu16* ptr; typedef gcu16* cptr; };
 
-// Workgroups per CU the step kernels are built and launched for.  With binary32 weights and
-// gradients the step is bound by its memory access pattern and two workgroups per CU (16
-// waves, up to 128 VGPRs) measured best; with 16-bit storage it moves 10 instead of 16 bytes
-// per parameter and is bound by instruction issue: three workgroups per CU (24 waves, 80
-// VGPRs, the 52 KB LDS map fits three times) measured 6 % faster there and 3 % slower with
-// binary32 storage.
-template <typename WT> struct Occupancy { static constexpr int kWgPerCu = 2; };
-template <> struct Occupancy<Bf16> { static constexpr int kWgPerCu = 3; };
-template <> struct Occupancy<F16> { static constexpr int kWgPerCu = 3; };
+// Launch shape of the step kernels by storage type of w and g.  With binary32 storage the step
+// is bound by its memory access pattern: two workgroups per CU (16 waves, up to 128 VGPRs) and
+// one job per draw measured best.  With 16-bit storage it moves 10 instead of 16 bytes per
+// parameter and is bound by instruction issue: three workgroups per CU (24 waves, 80 VGPRs; the
+// 52 KB LDS map fits three times) measured 6 % faster there (3 % slower with binary32), two jobs
+// per draw another 1 % (7 % slower with binary32: a wider window of addresses in flight).
+template <typename WT> struct Occupancy { static constexpr int kWgPerCu = 2, kSpan = 1; };
+template <> struct Occupancy<Bf16> { static constexpr int kWgPerCu = 3, kSpan = 2; };
+template <> struct Occupancy<F16> { static constexpr int kWgPerCu = 3, kSpan = 2; };
 
 template <typename WT> __device__ __forceinline__ void widen2(uint32_t pair, float& lo, float& hi);
 template <> __device__ __forceinline__ void widen2<Bf16>(uint32_t pair, float& lo, float& hi)
@@ -1122,7 +1122,7 @@ struct Lds {
     Exchange ex;
 };
 
-constexpr int kStepSpan = 1;        // jobs per draw of the optimizer-step kernels
+constexpr int kStepSpan = 1;        // jobs per draw of the optimizer-step kernels (binary32 storage; see Occupancy)
 constexpr int kQuantSpan = 4;       // the stand-alone quantizer does far less work per job
 
 // What a wave holds in one job: nothing, a tile of a tensor with 32-bit states (done in
@@ -1138,13 +1138,14 @@ __device__ __forceinline__ void adam8_walk(const StepArgs& a, const AdamScalars&
     const int part = wave % S::WPB;
     const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
     SgdScalars none{};
-    const bool once = single_draw<kStepSpan>(njobs);
+    constexpr int SPAN = Occupancy<WT>::kSpan;
+    const bool once = single_draw<SPAN>(njobs);
     int xpar = 0;
     for (int round = 0;; ++round) {
         if (once && round > 0) break;
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, round, njobs);
+        const int64_t j0 = next_draw<SPAN, false>(a.sched, &lds->box, round, njobs);
         if (j0 >= njobs) break;
-        for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
+        for (int k = 0; k < SPAN && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
             int kind = kNoTile;
             TensorDesc d{};
@@ -1175,7 +1176,7 @@ template <int B, typename WT>
 __global__ __launch_bounds__(kWgThreads, ((B < 256 && Occupancy<WT>::kWgPerCu == 2) ? 2 : 2 * Occupancy<WT>::kWgPerCu)) void adam8_kernel(StepArgs a, AdamScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
-    first_draw<kStepSpan>(a.sched, &lds.box);
+    first_draw<Occupancy<WT>::kSpan>(a.sched, &lds.box);
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     stage_second(lds.tab, a.qtab_u, threadIdx.x);
     __syncthreads();
@@ -1200,13 +1201,14 @@ __device__ __forceinline__ void sgd8_walk(const StepArgs& a, const SgdScalars& s
     const int part = wave % S::WPB;
     const int64_t njobs = (a.nunits + S::UPJ - 1) / S::UPJ;
     AdamScalars none{};
-    const bool once = single_draw<kStepSpan>(njobs);
+    constexpr int SPAN = Occupancy<WT>::kSpan;
+    const bool once = single_draw<SPAN>(njobs);
     int xpar = 0;
     for (int round = 0;; ++round) {
         if (once && round > 0) break;
-        const int64_t j0 = next_draw<kStepSpan, false>(a.sched, &lds->box, round, njobs);
+        const int64_t j0 = next_draw<SPAN, false>(a.sched, &lds->box, round, njobs);
         if (j0 >= njobs) break;
-        for (int k = 0; k < kStepSpan && j0 + k < njobs; ++k, xpar ^= 1) {
+        for (int k = 0; k < SPAN && j0 + k < njobs; ++k, xpar ^= 1) {
             const int64_t u = (j0 + k) * S::UPJ + wave / S::WPB;
             int kind = kNoTile;
             TensorDesc d{};
@@ -1237,7 +1239,7 @@ template <int B, typename WT>
 __global__ __launch_bounds__(kWgThreads, ((B < 256 && Occupancy<WT>::kWgPerCu == 2) ? 2 : 2 * Occupancy<WT>::kWgPerCu)) void sgd8_kernel(StepArgs a, SgdScalars sc)
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
-    first_draw<kStepSpan>(a.sched, &lds.box);
+    first_draw<Occupancy<WT>::kSpan>(a.sched, &lds.box);
     stage_first(lds.tab, a.qtab_s, threadIdx.x);
     __syncthreads();
     if (sc.wd != 0.0f) sgd8_walk<B, WT, true>(a, sc, &lds);
