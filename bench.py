@@ -41,6 +41,10 @@ WORKLOADS = {
 }
 
 
+# committed counter summaries (HBM bytes per launch) by workload
+TRAFFIC_PROFILE = {"1b": "adam8_kernel_1b_hbm_counters.md", "bf16_1b": "adam8_kernel_bf16_1b_hbm_counters.md"}
+
+
 def algorithmic_bytes(n: int, B: int) -> int:
     """Bytes the method must move per step: read w, g (4+4), codes of m, r (1+1); write w (4)
     and both codes (1+1); plus read+write of two absmax values per block."""
@@ -336,8 +340,11 @@ def main():
         "hbm_gbps": achieved, "pct_of_hbm_peak": 100.0 * achieved / HBM_PEAK_GBS,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": measured_traffic(os.path.join(ROOT, "profiles", "adam8_kernel_1b_hbm_counters.md"))
-                     if args.workload == "1b" else None,
+                     "traffic": measured_traffic(os.path.join(ROOT, "profiles", TRAFFIC_PROFILE.get(args.workload, "")))
+                     if args.workload in TRAFFIC_PROFILE and not args.block_size and not args.params else None,
+                     "traffic_source": ("profiles/%s: two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this workload, "
+                                        "committed together with the kernel; not measured in this run"
+                                        % TRAFFIC_PROFILE[args.workload]) if args.workload in TRAFFIC_PROFILE else None,
                      "kernel": kernel, "kernel_ms_avg": avg_kern_s * 1e3,
                      "kernel_ms_min": min(kern_ms), "kernel_ms_each": [round(x, 4) for x in kern_ms],
                      "algorithmic_bytes_per_launch": alg},
