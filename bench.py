@@ -350,7 +350,7 @@ def main():
                      "algorithmic_bytes_per_launch": alg},
     }
     if not args.no_cpu and cpu_args is not None:
-        out["cpu_baseline"] = cpu_baseline(*cpu_args, args.cpu_sample, steps=2)
+        out["cpu_baseline"] = cpu_baseline(*cpu_args, args.cpu_sample, steps=4)
     print(json.dumps(out))
 
 

@@ -54,9 +54,10 @@
  *     the same time (a graph replayed concurrently with itself, or two
  *     executable graphs instantiated from one capture running concurrently),
  *     or destroy a stream while a kernel of this library still runs on it.
- *     The device entry points enqueue exactly one kernel (no memset, no copy),
- *     so they can be captured once each kernel has been launched eagerly a
- *     first time (the first launch queries occupancy and the counter address).
+ *     The device entry points enqueue exactly one kernel
+ *     (q8_multi_adam8bit_step_noalloc: a few) and no memset or copy, so they
+ *     can be captured once each kernel has been launched eagerly a first time
+ *     (the first launch queries occupancy and the counter address).
  */
 #ifndef Q8OPT_H
 #define Q8OPT_H
@@ -146,6 +147,12 @@ Q8_API q8_status q8_dequantize_blockwise(const void* qtable, const uint8_t* TQ, 
  * states, not their quantized values.  1-beta1 and 1-beta2 are formed in
  * binary32 on the host.  `t` (1-based step count) is used only with
  * Q8_FLAG_BIAS_CORRECTION.
+ * Extensions (not printed in Eq. adam; one binary32 operation per step as above):
+ *   Q8_FLAG_BIAS_CORRECTION:  rs = sqrt(r)*c;  d = rs + eps;  w = w - alpha_t*(m/d)
+ *     with alpha_t = alpha/(1-beta1^t) and c = 1/sqrt(1-beta2^t), each evaluated in
+ *     binary64 from the binary32 hyper-parameters and rounded once to binary32;
+ *   Q8_FLAG_DECOUPLED_WD (wd != 0):  w = w - (alpha*wd)*w  before the step is
+ *     subtracted, and g is left alone.
  * In place on w, m_q, r_q, N_m, N_r (device); g is read only (device).
  */
 Q8_API q8_status q8_adam8bit_step(float* w, const float* g,

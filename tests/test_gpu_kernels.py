@@ -427,3 +427,39 @@ def test_traffic_probe_leaves_everything_unchanged(q8, tabs):
     probe(w, g, m, r, tabs[0], tabs[1])
     assert np.array_equal(w.cpu().numpy().view(np.uint32), w0.view(np.uint32)) and np.array_equal(g.cpu().numpy(), g0)
     assert np.array_equal(m.cpu().numpy(), m0) and np.array_equal(r.cpu().numpy(), r0)
+
+
+@pytest.mark.parametrize("B", [256, 2048])
+def test_nonfinite_gradients_stay_inside_their_blocks(q8, tabs, B):
+    """Results for NaN / Inf inputs are unspecified, but the call completes, nothing is read or
+    written out of bounds (every table key is clamped into the LDS map), and -- blocks being
+    independent -- every block without such an input still matches the oracle bit for bit."""
+    n = 20 * B + 77
+    w_ref = synth.uniform_weights(1300, 0, n)
+    st = H.zero_state(n, B)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    bad_blocks = [1, 7, 12]
+    for t in range(1, 4):
+        g = synth.normal_grad(1300, 0, t, n, 1e-3)
+        g[1 * B + 5] = np.nan
+        g[7 * B] = np.inf
+        g[12 * B + B - 1] = -np.inf
+        g[12 * B + 3] = np.nan
+        q8.adam8bit_step(w, dev(g), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        torch.cuda.synchronize()
+        with np.errstate(all="ignore"):
+            H.oracle_adam8(w_ref, g, st, B, t=t, split=False)
+        keep = np.ones(n, bool)
+        for b in bad_blocks:
+            keep[b * B:(b + 1) * B] = False
+        bkeep = np.ones(oracle.nblocks(n, B), bool)
+        bkeep[bad_blocks] = False
+        for k in ("m_q", "r_q"):
+            assert np.array_equal(d[k].cpu().numpy()[keep], st[k][keep]), (t, k)
+        for k in ("N_m", "N_r"):
+            assert np.array_equal(d[k].cpu().numpy().view(np.uint32)[bkeep], st[k].view(np.uint32)[bkeep]), (t, k)
+        assert np.array_equal(w.cpu().numpy().view(np.uint32)[keep], w_ref.view(np.uint32)[keep])
+        # keep the two trajectories together where the results are unspecified
+        for k in d:
+            d[k].copy_(dev(st[k]))
+        w.copy_(dev(w_ref))
