@@ -155,28 +155,51 @@ constexpr uint32_t kLdsLastKey = kLdsBytes - 1;
 static_assert(kLdsU + kLutHalf <= kLdsNeg && kLdsNeg + kLutHalf <= kLdsQ1 && kLdsT2 + 1024 <= kLdsBytes, "LDS map");
 static_assert(kLdsU + 0x7fff < kLdsBytes, "every 15-bit key of the second table stays inside the map");
 
-__device__ __forceinline__ void copy16(unsigned char* dst, const unsigned char* src, int bytes, int tid)
-{
-    gcuint4* s4 = (gcuint4*)src;
-    v4u* d4 = reinterpret_cast<v4u*>(dst);
-    for (int i = tid; i < bytes / 16; i += kWgThreads) d4[i] = s4[i];
-}
+// Staging of the search tables.  A copy of BYTES bytes takes ceil(BYTES / 16 / kWgThreads)
+// 16-byte pieces per thread; all loads of all copies are issued before the first LDS store
+// waits for its data, so that the workgroup pays one round trip to L2 for its tables, not
+// one per piece.
+template <int BYTES>
+struct Copy16 {
+    static constexpr int N = BYTES / 16, K = (N + kWgThreads - 1) / kWgThreads;
+    v4u v[K];
+    __device__ __forceinline__ void load(const unsigned char* src, int tid)
+    {
+        gcuint4* s4 = (gcuint4*)src;
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (k * kWgThreads + tid < N) v[k] = s4[k * kWgThreads + tid];
+    }
+    __device__ __forceinline__ void store(unsigned char* dst, int tid) const
+    {
+        v4u* d4 = reinterpret_cast<v4u*>(dst);
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            if (k * kWgThreads + tid < N) d4[k * kWgThreads + tid] = v[k];
+    }
+};
 
-// first table: both signs
-__device__ __forceinline__ void stage_first(unsigned char* lds, const void* qtab, int tid)
+// first table (both signs) and, if qtab_u != nullptr, the second one (non-negative half only)
+__device__ __forceinline__ void stage_tables(unsigned char* lds, const void* qtab_s, const void* qtab_u, int tid)
 {
-    const unsigned char* blob = static_cast<const unsigned char*>(qtab);
-    copy16(lds, blob + kOffLut, kLutHalf, tid);
-    copy16(lds + kLdsNeg, blob + kOffLut + 0x8000, kLutHalf, tid);
-    copy16(lds + kLdsQ1, blob + kOffQmap, 2048, tid);
-}
-
-// second table: non-negative half only
-__device__ __forceinline__ void stage_second(unsigned char* lds, const void* qtab, int tid)
-{
-    const unsigned char* blob = static_cast<const unsigned char*>(qtab);
-    copy16(lds + kLdsU, blob + kOffLut, kLutHalf, tid);
-    copy16(lds + kLdsQ2, blob + kOffQmap, 2048, tid);
+    const unsigned char* s = static_cast<const unsigned char*>(qtab_s);
+    const unsigned char* u = static_cast<const unsigned char*>(qtab_u);
+    Copy16<kLutHalf> pos, neg, upos;
+    Copy16<2048> q1, q2;
+    pos.load(s + kOffLut, tid);
+    neg.load(s + kOffLut + 0x8000, tid);
+    q1.load(s + kOffQmap, tid);
+    if (u) {
+        upos.load(u + kOffLut, tid);
+        q2.load(u + kOffQmap, tid);
+    }
+    pos.store(lds, tid);
+    neg.store(lds + kLdsNeg, tid);
+    q1.store(lds + kLdsQ1, tid);
+    if (u) {
+        upos.store(lds + kLdsU, tid);
+        q2.store(lds + kLdsQ2, tid);
+    }
 }
 
 // Nearest code of x (Eq. quant2) by bucket lookup + one exact threshold compare.
@@ -1177,8 +1200,7 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256 && Occupancy<WT>::kWgPerCu ==
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<Occupancy<WT>::kSpan>(a.sched, &lds.box);
-    stage_first(lds.tab, a.qtab_s, threadIdx.x);
-    stage_second(lds.tab, a.qtab_u, threadIdx.x);
+    stage_tables(lds.tab, a.qtab_s, a.qtab_u, threadIdx.x);
     __syncthreads();
     if (sc.bias) {
         if (sc.wd_mode == 0) adam8_walk<B, WT, 0, true>(a, sc, &lds);
@@ -1240,7 +1262,7 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256 && Occupancy<WT>::kWgPerCu ==
 {
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<Occupancy<WT>::kSpan>(a.sched, &lds.box);
-    stage_first(lds.tab, a.qtab_s, threadIdx.x);
+    stage_tables(lds.tab, a.qtab_s, nullptr, threadIdx.x);
     __syncthreads();
     if (sc.wd != 0.0f) sgd8_walk<B, WT, true>(a, sc, &lds);
     else sgd8_walk<B, WT, false>(a, sc, &lds);
@@ -1255,7 +1277,7 @@ __global__ __launch_bounds__(kWgThreads, ((B < 256) ? 2 : kMinWavesPerEu)) void 
     using S = Shape<B>;
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<kQuantSpan>(sched, &lds.box);
-    stage_first(lds.tab, qtab, threadIdx.x);
+    stage_tables(lds.tab, qtab, nullptr, threadIdx.x);
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

@@ -15,8 +15,7 @@ __global__ __launch_bounds__(kWgThreads, kMinWavesPerEu) void traffic_probe_kern
     using S = Shape<2048>;
     __shared__ __attribute__((aligned(16))) Lds lds;
     first_draw<kStepSpan>(a.sched, &lds.box);
-    stage_first(lds.tab, a.qtab_s, threadIdx.x);
-    stage_second(lds.tab, a.qtab_u, threadIdx.x);
+    stage_tables(lds.tab, a.qtab_s, a.qtab_u, threadIdx.x);
     __syncthreads();
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
