@@ -71,7 +71,12 @@ def test_long_launch_overlapped_by_many_short_launches(q8, tabs):
     chk = H.WholeTensorParity("long launch", w, B)
     smalls = [Small(1000 + k, 20_000 + 777 * k, 2048 if k % 2 else 256) for k in range(3)]
     sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    # first launches of a process load code and query occupancy: keep them out of the overlap
+    warm = [Small(1100 + k, 5_000, 2048 if k % 2 else 256) for k in range(2)]
+    for s in warm:
+        s.launch(q8, tabs)
     torch.cuda.synchronize()
+    overlapped = 0
     for t in range(1, 3):
         chk.oracle_step(g, t)
         start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -86,12 +91,12 @@ def test_long_launch_overlapped_by_many_short_launches(q8, tabs):
                 smalls[k % 3].launch(q8, tabs)
             last_b.record()
         torch.cuda.synchronize()
-        # the short launches started before the long kernel ended (they did overlap)
-        assert start.elapsed_time(first_b) < start.elapsed_time(end), "stream B did not overlap the long launch"
+        overlapped += start.elapsed_time(first_b) < start.elapsed_time(end)      # stream B started before the long kernel ended
         bad = chk.compare(w, d, "long launch step %d" % t)
         assert bad == 0
     for k, s in enumerate(smalls):
         s.check("small tensor %d after %d launches" % (k, s.t))
+    assert overlapped >= 1, "stream B never overlapped the long launch: the test did not exercise what it is for"
     H.report_parity("long launch overlapped by 300 short launches (1e9 parameters, every entry)", [chk])
 
 
@@ -176,3 +181,101 @@ def test_more_captures_than_reserved_counters(q8, tabs):
         for _ in range(steps[k]):
             H.oracle_adam8(w_ref, g, st, B)
         H.assert_state_equal("tensor %d after %d steps" % (k, steps[k]), ds[k], st, ws[k], w_ref)
+
+
+def test_fixed_order_fallback_for_every_kernel(q8, tabs):
+    """After test_more_captures_than_reserved_counters every reserved counter is taken, so each
+    further captured launch runs with the fixed assignment of work: SGD, the stand-alone
+    quantizer and the bfloat16 Adam step, replayed twice, against the oracle."""
+    import oracle
+    n, B = 5_000_000 + 1234, 2048
+    qs, _ = H.codebooks()
+    # make sure the reserved counters are used up even when this test runs alone
+    side = torch.cuda.Stream()
+    dummy = Small(4100, 50_000, 2048)
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dummy.launch(q8, tabs)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for _ in range(70):
+        gph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gph):
+            q8.adam8bit_step(dummy.w, dummy.gd, dummy.d["m_q"], dummy.d["r_q"], dummy.d["N_m"], dummy.d["N_r"],
+                             tabs[0], tabs[1], dummy.B, **H.ADAM)
+        del gph
+    # SGD
+    w_ref = synth.uniform_weights(4000, 0, n); g = synth.normal_grad(4000, 0, 1, n, 1e-2)
+    st = H.zero_state(n, B, adam=False)
+    w, gd = dev(w_ref), dev(g)
+    d = {k: dev(v) for k, v in st.items()}
+    # quantizer
+    T = synth.normal_grad(4001, 0, 1, n, 1.0)
+    Td = dev(T); TQ = torch.empty(n, dtype=torch.uint8, device="cuda"); N = torch.empty(oracle.nblocks(n, B), device="cuda")
+    # bfloat16 Adam
+    wb_ref = synth.bf16_bits(synth.uniform_weights(4002, 0, n)); gb = synth.bf16_bits(synth.normal_grad(4002, 0, 1, n, 1e-3))
+    stb = H.zero_state(n, B)
+    wb = torch.from_numpy(wb_ref.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    gbd = torch.from_numpy(gb.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    db = {k: dev(v) for k, v in stb.items()}
+    with torch.cuda.stream(side):                    # eager warm-up of the three kernels (they are not in any cache yet)
+        q8.sgd8bit_step(w, gd, d["m_q"], d["N_m"], tabs[0], B, **H.SGD, weight_decay=1e-4)
+        q8.quantize_blockwise(tabs[0], Td, B, TQ, N)
+        q8.adam8bit_step_bf16(wb, gbd, db["m_q"], db["r_q"], db["N_m"], db["N_r"], tabs[0], tabs[1], B, **H.ADAM)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    H.oracle_sgd8(w_ref, g, st, B, wd=1e-4)
+    H.oracle_adam8(wb_ref, gb, stb, B, bf16=True)
+    gph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gph):
+        q8.sgd8bit_step(w, gd, d["m_q"], d["N_m"], tabs[0], B, **H.SGD, weight_decay=1e-4)
+        q8.quantize_blockwise(tabs[0], Td, B, TQ, N)
+        q8.adam8bit_step_bf16(wb, gbd, db["m_q"], db["r_q"], db["N_m"], db["N_r"], tabs[0], tabs[1], B, **H.ADAM)
+    for rep in range(2):
+        TQ.fill_(3); N.fill_(-1.0)
+        gph.replay()
+        torch.cuda.synchronize()
+        H.oracle_sgd8(w_ref, g, st, B, wd=1e-4)
+        H.oracle_adam8(wb_ref, gb, stb, B, bf16=True)
+        H.assert_state_equal("sgd replay %d" % rep, d, st, w, w_ref)
+        TQ_ref, N_ref = oracle.quantize_blockwise(qs, T, B)
+        assert np.array_equal(TQ.cpu().numpy(), TQ_ref) and np.array_equal(N.cpu().numpy().view(np.uint32), N_ref.view(np.uint32))
+        for k in stb:
+            a, b = db[k].cpu().numpy(), stb[k]
+            if a.dtype == np.float32:
+                a, b = a.view(np.uint32), b.view(np.uint32)
+            assert np.array_equal(a, b), (rep, k)
+        assert np.array_equal(wb.view(torch.int16).cpu().numpy().view(np.uint16), wb_ref)
+
+
+def test_per_thread_default_stream_counts_once_per_thread(q8, tabs):
+    """Two host threads launch on the per-thread default stream (the same handle value, two
+    different streams): each thread gets its own counter.  Called through the C ABI directly."""
+    import threading
+    L = q8.lib()
+    PER_THREAD = 2                                     # hipStreamPerThread
+    n, B, steps = (1 << 20) + 555, 2048, 12
+    items = [Small(5000 + k, n, B) for k in range(2)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(k):
+        try:
+            s = items[k]
+            for t in range(1, steps + 1):
+                rc = L.q8_adam8bit_step(s.w.data_ptr(), s.gd.data_ptr(), s.d["m_q"].data_ptr(), s.d["r_q"].data_ptr(),
+                                        s.d["N_m"].data_ptr(), s.d["N_r"].data_ptr(), tabs[0].data_ptr(), tabs[1].data_ptr(),
+                                        n, B, H.ADAM["alpha"], H.ADAM["beta1"], H.ADAM["beta2"], H.ADAM["eps"], 0.0, t, 0, PER_THREAD)
+                assert rc == 0, rc
+            s.t = steps
+        except Exception as e:
+            errors.append(e)
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for k, s in enumerate(items):
+        s.check("thread %d on its per-thread default stream" % k)
