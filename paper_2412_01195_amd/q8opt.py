@@ -121,17 +121,38 @@ def host_nearest_code(qtable: np.ndarray, x) -> int:
 
 
 # ----------------------------------------------------------------------------- device side
-def _ptr(t, dtype_name: Optional[str] = None) -> int:
-    """Device address of a torch CUDA tensor (or pass an int / None through)."""
-    if t is None:
-        return 0
-    if isinstance(t, int):
-        return t
-    if not t.is_cuda or not t.is_contiguous():
-        raise ValueError("expected a contiguous CUDA tensor")
-    if dtype_name is not None and str(t.dtype) != "torch." + dtype_name:
-        raise ValueError("expected dtype %s, got %s" % (dtype_name, t.dtype))
-    return t.data_ptr()
+def _ptrs(*specs):
+    """Device addresses of torch CUDA tensors; a spec is (tensor | int | None, dtype name,
+    elements the call will touch, name).  Integers (raw device addresses) and None pass
+    through.  The C ABI sees plain pointers and cannot check sizes, so a tensor of the wrong
+    type or too small is refused here instead of being overrun on the device; types and sizes
+    of all arguments are checked before their placement."""
+    for t, dtype_name, need, what in specs:
+        if t is None or isinstance(t, (int, np.integer)):
+            continue
+        if dtype_name is not None and str(t.dtype) != "torch." + dtype_name:
+            raise ValueError("%s: expected dtype %s, got %s" % (what, dtype_name, t.dtype))
+        if t.numel() < need:
+            raise ValueError("%s holds %d elements, the call needs %d" % (what, t.numel(), need))
+    out = []
+    for t, dtype_name, need, what in specs:
+        if t is None:
+            out.append(0)
+        elif isinstance(t, (int, np.integer)):
+            out.append(int(t))
+        elif not t.is_cuda or not t.is_contiguous():
+            raise ValueError("%s: expected a contiguous CUDA tensor" % what)
+        else:
+            out.append(t.data_ptr())
+    return out
+
+
+def _blocks(n: int, B: int) -> int:
+    return -(-n // B) if B > 0 else 0          # an invalid B is reported by the library (Q8_EBLOCK)
+
+
+def _qtab(t, what: str):
+    return (t, "uint8", qtable_bytes(), what)
 
 
 def _stream() -> int:
@@ -147,29 +168,33 @@ def upload_qtable(blob: np.ndarray, device="cuda"):
 
 def quantize_blockwise(qtable, T, B: int, TQ, N, n: Optional[int] = None):
     n = T.numel() if n is None else n
-    _check(lib().q8_quantize_blockwise(_ptr(qtable, "uint8"), _ptr(T, "float32"), n, B,
-                                       _ptr(TQ, "uint8"), _ptr(N, "float32"), _stream()), "q8_quantize_blockwise")
+    q, t, tq, nn = _ptrs(_qtab(qtable, "qtable"), (T, "float32", n, "T"), (TQ, "uint8", n, "TQ"),
+                         (N, "float32", _blocks(n, B), "N"))
+    _check(lib().q8_quantize_blockwise(q, t, n, B, tq, nn, _stream()), "q8_quantize_blockwise")
 
 
 def dequantize_blockwise(qtable, TQ, N, B: int, TD, n: Optional[int] = None):
     n = TQ.numel() if n is None else n
-    _check(lib().q8_dequantize_blockwise(_ptr(qtable, "uint8"), _ptr(TQ, "uint8"), _ptr(N, "float32"), n, B,
-                                         _ptr(TD, "float32"), _stream()), "q8_dequantize_blockwise")
+    q, tq, nn, td = _ptrs(_qtab(qtable, "qtable"), (TQ, "uint8", n, "TQ"), (N, "float32", _blocks(n, B), "N"),
+                          (TD, "float32", n, "TD"))
+    _check(lib().q8_dequantize_blockwise(q, tq, nn, n, B, td, _stream()), "q8_dequantize_blockwise")
 
 
 def _adam(entry: str, wg_dtype: str, w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, B,
           alpha, beta1, beta2, eps, weight_decay, t, flags, n):
     n = w.numel() if n is None else n
-    _check(getattr(lib(), entry)(_ptr(w, wg_dtype), _ptr(g, wg_dtype), _ptr(m_q, "uint8"), _ptr(r_q, "uint8"),
-                                 _ptr(N_m, "float32"), _ptr(N_r, "float32"),
-                                 _ptr(qtable_signed, "uint8"), _ptr(qtable_unsigned, "uint8"), n, B,
-                                 alpha, beta1, beta2, eps, weight_decay, t, flags, _stream()), entry)
+    nb = _blocks(n, B)
+    p = _ptrs((w, wg_dtype, n, "w"), (g, wg_dtype, n, "g"), (m_q, "uint8", n, "m_q"), (r_q, "uint8", n, "r_q"),
+              (N_m, "float32", nb, "N_m"), (N_r, "float32", nb, "N_r"),
+              _qtab(qtable_signed, "qtable_signed"), _qtab(qtable_unsigned, "qtable_unsigned"))
+    _check(getattr(lib(), entry)(*p, n, B, alpha, beta1, beta2, eps, weight_decay, t, flags, _stream()), entry)
 
 
 def _sgd(entry: str, wg_dtype: str, w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n):
     n = w.numel() if n is None else n
-    _check(getattr(lib(), entry)(_ptr(w, wg_dtype), _ptr(g, wg_dtype), _ptr(m_q, "uint8"), _ptr(N_m, "float32"),
-                                 _ptr(qtable_signed, "uint8"), n, B, alpha, beta, weight_decay, _stream()), entry)
+    p = _ptrs((w, wg_dtype, n, "w"), (g, wg_dtype, n, "g"), (m_q, "uint8", n, "m_q"),
+              (N_m, "float32", _blocks(n, B), "N_m"), _qtab(qtable_signed, "qtable_signed"))
+    _check(getattr(lib(), entry)(*p, n, B, alpha, beta, weight_decay, _stream()), entry)
 
 
 def adam8bit_step(w, g, m_q, r_q, N_m, N_r, qtable_signed, qtable_unsigned, B: int,
@@ -208,13 +233,23 @@ def sgd8bit_step_f16(w, g, m_q, N_m, qtable_signed, B: int, alpha, beta, weight_
     _sgd("q8_sgd8bit_step_f16", "float16", w, g, m_q, N_m, qtable_signed, B, alpha, beta, weight_decay, n)
 
 
-def _tensor_array(tensors: Sequence[dict], wg: str):
+_FIELDS = (("w", None), ("g", None), ("m_q", "uint8"), ("r_q", "uint8"), ("N_m", "float32"), ("N_r", "float32"),
+           ("m_f32", "float32"), ("r_f32", "float32"))
+
+
+def _tensor_array(tensors: Sequence[dict], wg: str, B: int):
+    specs = []
+    for i, t in enumerate(tensors):
+        n = t["w"].numel()
+        for key, dt in _FIELDS:
+            need = _blocks(n, B) if key in ("N_m", "N_r") else n
+            specs.append((t.get(key), dt or wg, need, "tensor %d: %s" % (i, key)))
+    ptrs = _ptrs(*specs)
     arr = (q8_tensor * len(tensors))()
     for i, t in enumerate(tensors):
-        arr[i].w = _ptr(t["w"], wg); arr[i].g = _ptr(t["g"], wg); arr[i].n = t["w"].numel()
-        arr[i].m_q = _ptr(t.get("m_q"), "uint8"); arr[i].r_q = _ptr(t.get("r_q"), "uint8")
-        arr[i].N_m = _ptr(t.get("N_m"), "float32"); arr[i].N_r = _ptr(t.get("N_r"), "float32")
-        arr[i].m_f32 = _ptr(t.get("m_f32"), "float32"); arr[i].r_f32 = _ptr(t.get("r_f32"), "float32")
+        arr[i].n = t["w"].numel()
+        for k, (key, _) in enumerate(_FIELDS):
+            setattr(arr[i], key, ptrs[i * len(_FIELDS) + k])
     return arr
 
 
@@ -222,9 +257,9 @@ def multi_adam8bit_step_noalloc(tensors: Sequence[dict], B: int, qtable_signed, 
                                 alpha, beta1, beta2, eps, weight_decay=0.0, t=1, flags=0):
     """q8_multi_adam8bit_step_noalloc: one Adam step over a list of fp32 tensors (dicts as for Plan)
     without a plan and without any device allocation by the library."""
-    arr = _tensor_array(tensors, "float32")
-    _check(lib().q8_multi_adam8bit_step_noalloc(arr, len(tensors), B, _ptr(qtable_signed, "uint8"),
-                                                _ptr(qtable_unsigned, "uint8"), alpha, beta1, beta2, eps,
+    arr = _tensor_array(tensors, "float32", B)
+    qs, qu = _ptrs(_qtab(qtable_signed, "qtable_signed"), _qtab(qtable_unsigned, "qtable_unsigned"))
+    _check(lib().q8_multi_adam8bit_step_noalloc(arr, len(tensors), B, qs, qu, alpha, beta1, beta2, eps,
                                                 weight_decay, t, flags, _stream()),
            "q8_multi_adam8bit_step_noalloc")
 
@@ -241,7 +276,7 @@ class Plan:
         wg = wg_dtype or ("bfloat16" if bf16 else "float32")
         if wg not in ("float32", "bfloat16", "float16"):
             raise ValueError("wg_dtype must be float32, bfloat16 or float16")
-        arr = _tensor_array(tensors, wg)
+        arr = _tensor_array(tensors, wg, B)
         h = C.c_void_p()
         create = {"float32": lib().q8_plan_create, "bfloat16": lib().q8_plan_create_bf16,
                   "float16": lib().q8_plan_create_f16}[wg]
@@ -250,12 +285,14 @@ class Plan:
 
     def multi_adam8bit_step(self, qtable_signed, qtable_unsigned, alpha, beta1, beta2, eps,
                             weight_decay=0.0, t=1, flags=0):
-        _check(lib().q8_multi_adam8bit_step(self._h, _ptr(qtable_signed, "uint8"), _ptr(qtable_unsigned, "uint8"),
+        qs, qu = _ptrs(_qtab(qtable_signed, "qtable_signed"), _qtab(qtable_unsigned, "qtable_unsigned"))
+        _check(lib().q8_multi_adam8bit_step(self._h, qs, qu,
                                             alpha, beta1, beta2, eps, weight_decay, t, flags, _stream()),
                "q8_multi_adam8bit_step")
 
     def multi_sgd8bit_step(self, qtable_signed, alpha, beta, weight_decay=0.0):
-        _check(lib().q8_multi_sgd8bit_step(self._h, _ptr(qtable_signed, "uint8"), alpha, beta, weight_decay,
+        qs, = _ptrs(_qtab(qtable_signed, "qtable_signed"))
+        _check(lib().q8_multi_sgd8bit_step(self._h, qs, alpha, beta, weight_decay,
                                            _stream()), "q8_multi_sgd8bit_step")
 
     def destroy(self):

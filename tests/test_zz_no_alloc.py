@@ -106,7 +106,7 @@ def test_noalloc_limits_and_arguments(q8, tabs):
         q8.multi_adam8bit_step_noalloc([one] * 1025, 2048, tabs[0], tabs[1], **H.ADAM)
     assert err.value.status == q8.ELIMIT
     # more units than the workspace holds: described, never touched (n is only a number here)
-    arr = q8._tensor_array([one], "float32")
+    arr = q8._tensor_array([one], "float32", 2048)
     arr[0].n = (1 << 17) * 2048 + 1
     st = L.q8_multi_adam8bit_step_noalloc(arr, 1, 2048, tabs[0].data_ptr(), tabs[1].data_ptr(), 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 0, None)
     assert st == q8.ELIMIT
