@@ -116,9 +116,19 @@ def cpu_baseline(w_dev, g_dev, B: int, sample: int, steps: int):
         for _ in range(steps):
             list(ex.map(run, range(cores)))
         dt = time.perf_counter() - t0
+    # the sequential definition itself: one thread, the first 2^23 of those parameters
+    n1 = min(n, 1 << 23) // B * B
+    s1, b1 = slice(0, n1), n1 // B
+    t1 = time.perf_counter()
+    for _ in range(2):
+        oracle.adam8bit_step(w[s1], g[s1], mq[s1], rq[s1], Nm[:b1], Nr[:b1], qs, qu, B,
+                             ADAM["alpha"], ADAM["beta1"], ADAM["beta2"], ADAM["eps"], 0.0, 1, 0)
+    dt1 = time.perf_counter() - t1
     return dict(value=n * steps / dt, unit="params/s", cores=cores, kind="oracle",
                 sample="first %d params of the workload, %d Adam steps after one untimed step, "
-                       "block ranges split over %d threads" % (n, steps, cores))
+                       "block ranges split over %d threads" % (n, steps, cores),
+                one_core=dict(value=n1 * 2 / dt1, unit="params/s",
+                              sample="first %d params, 2 further Adam steps on one thread" % n1))
 
 
 def build_workload(name, torch, q8opt, dev):
