@@ -238,3 +238,42 @@ def test_f16_subnormal_and_large_weights(q8, tabs):
         q8.adam8bit_step_f16(w_d, dev16(g), st_d["m_q"], st_d["r_q"], st_d["N_m"], st_d["N_r"], tabs[0], tabs[1], B,
                              weight_decay=1e-2, t=t, **hp)
         assert_all_equal("f16 range step %d" % t, w_d, w, st_d, st)
+
+
+def test_f16_one_billion_parameters_every_entry(q8, tabs):
+    """10^9 parameters at B = 2048 in the benchmark's launch configuration (the workload
+    `f16_1b` of bench.py), three steps with decoupled decay and bias correction: the oracle
+    advances every block on the host threads; stored weights, codes and block maxima are
+    compared entry by entry on the device after every step and must be identical."""
+    n, B, chunk = 1_000_000_000, 2048, 1 << 27
+    gen = torch.Generator(device="cuda"); gen.manual_seed(21)
+    w_d = torch.empty(n, dtype=torch.float16, device="cuda")
+    g_d = torch.empty(n, dtype=torch.float16, device="cuda")
+    for lo in range(0, n, chunk):                                    # generate in pieces: bounded binary32 temporaries
+        hi = min(n, lo + chunk)
+        w_d[lo:hi] = (torch.rand(hi - lo, device="cuda", generator=gen) - 0.5).mul_(0.2).to(torch.float16)
+    st_d = dev_state(H.zero_state(n, B))
+    w_h = host16(w_d)
+    st_h = H.zero_state(n, B)
+    flags = q8.FLAG_BIAS_CORRECTION | q8.FLAG_DECOUPLED_WD
+    for t in range(1, 4):
+        for lo in range(0, n, chunk):
+            hi = min(n, lo + chunk)
+            g_d[lo:hi] = torch.randn(hi - lo, device="cuda", generator=gen).mul_(1e-3).to(torch.float16)
+        q8.adam8bit_step_f16(w_d, g_d, st_d["m_q"], st_d["r_q"], st_d["N_m"], st_d["N_r"], tabs[0], tabs[1], B,
+                              weight_decay=1e-2, t=t, flags=flags, **H.ADAM)
+        H.oracle_adam8(w_h, host16(g_d), st_h, B, wd=1e-2, t=t, flags=flags, f16=True)
+        for k in ("N_m", "N_r"):
+            ref = torch.from_numpy(st_h[k]).cuda()
+            bad = int((st_d[k].view(torch.int32) != ref.view(torch.int32)).sum())
+            assert bad == 0, "step %d: %s differs in %d blocks" % (t, k, bad)
+        for lo in range(0, n, chunk):
+            hi = min(n, lo + chunk)
+            for k in ("m_q", "r_q"):
+                bad = int((st_d[k][lo:hi] != torch.from_numpy(st_h[k][lo:hi]).cuda()).sum())
+                assert bad == 0, "step %d: %s differs in %d entries of [%d, %d)" % (t, k, bad, lo, hi)
+            ref = torch.from_numpy(w_h[lo:hi].view(np.int16)).cuda()
+            bad = int((w_d[lo:hi].view(torch.int16) != ref).sum())
+            assert bad == 0, "step %d: %d stored weights differ in [%d, %d)" % (t, bad, lo, hi)
+    H.report("f16 storage, 1e9 parameters, B=2048, 3 steps (AdamW with bias correction): every stored weight, "
+             "code and block maximum identical to the oracle's")
