@@ -415,3 +415,71 @@ def test_config5_full_size_every_entry(q8, tabs):
             print("config 5 step %d: %d mismatching codes" % (t, bad), flush=True)
     plan.destroy()
     H.report_parity("config 5 (64 x 1 562 500 parameters, B=256, 50 steps, every entry after every step)", chks)
+
+
+def _by_block_ranges(n, B, fn):
+    """fn(element slice, block slice) over disjoint block ranges on the host threads (blocks
+    are independent, so the split changes nothing)."""
+    nb = oracle.nblocks(n, B)
+    nthr = H.host_threads()
+    per = -(-nb // nthr)
+    parts = [(k * per, min(nb, (k + 1) * per)) for k in range(nthr) if k * per < nb]
+    list(H.pool().map(lambda p: fn(slice(p[0] * B, min(n, p[1] * B)), slice(p[0], p[1])), parts))
+
+
+def test_sgd_quantize_dequantize_one_billion_every_entry(q8, tabs):
+    """The other 10^9-element workloads of bench.py (sgd1b, quant1b, dequant1b) in their launch
+    configuration, every entry against the oracle: two SGD-momentum steps with coupled decay on
+    10^9 parameters, then that tensor quantized stand-alone with both codebooks' rules (signed map,
+    and the unsigned map on its absolute values) and dequantized again."""
+    n, B, chunk = 1_000_000_000, 2048, 1 << 27
+    qs, qu = H.codebooks()
+    gen = torch.Generator(device="cuda"); gen.manual_seed(33)
+    w_d = torch.empty(n, device="cuda"); g_d = torch.empty(n, device="cuda")
+    w_d.uniform_(-0.1, 0.1, generator=gen)
+    st_d = {k: torch.from_numpy(v).cuda() for k, v in H.zero_state(n, B, adam=False).items()}
+    w_h = w_d.cpu().numpy()
+    st_h = H.zero_state(n, B, adam=False)
+    g_h = torch.empty(n, dtype=torch.float32, pin_memory=True)
+
+    def same_bits(dev_t, host_a, what):
+        for lo in range(0, host_a.size, chunk):
+            hi = min(host_a.size, lo + chunk)
+            ref = torch.from_numpy(host_a[lo:hi]).cuda()
+            a, b = dev_t[lo:hi], ref
+            if a.dtype == torch.float32:
+                a, b = a.view(torch.int32), b.view(torch.int32)
+            bad = int((a != b).sum())
+            assert bad == 0, "%s differs in %d entries of [%d, %d)" % (what, bad, lo, hi)
+
+    for t in (1, 2):
+        g_d.normal_(0.0, 1e-2, generator=gen)
+        q8.sgd8bit_step(w_d, g_d, st_d["m_q"], st_d["N_m"], tabs[0], B, weight_decay=1e-4, **H.SGD)
+        g_h.copy_(g_d); torch.cuda.synchronize()
+        g_np = g_h.numpy()
+        _by_block_ranges(n, B, lambda e, b: oracle.sgd8bit_step(w_h[e], g_np[e], st_h["m_q"][e], st_h["N_m"][b], qs, B,
+                                                                H.SGD["alpha"], H.SGD["beta"], 1e-4))
+        same_bits(st_d["N_m"], st_h["N_m"], "SGD step %d: block maxima" % t)
+        same_bits(st_d["m_q"], st_h["m_q"], "SGD step %d: codes" % t)
+        same_bits(w_d, w_h, "SGD step %d: weights" % t)
+    del g_d, g_h
+    nb = oracle.nblocks(n, B)
+    TQ = torch.empty(n, dtype=torch.uint8, device="cuda"); N = torch.empty(nb, device="cuda"); TD = torch.empty(n, device="cuda")
+    for signed, q, tab in ((True, qs, tabs[0]), (False, qu, tabs[1])):
+        T_h = w_h if signed else np.abs(w_h)
+        T_d = w_d if signed else w_d.abs()
+        TQ_ref = np.empty(n, np.uint8); N_ref = np.empty(nb, np.float32); TD_ref = np.empty(n, np.float32)
+
+        def one(e, b):
+            TQ_ref[e], N_ref[b] = oracle.quantize_blockwise(q, T_h[e], B)
+            TD_ref[e] = oracle.dequantize_blockwise(q, TQ_ref[e], N_ref[b], B)
+        _by_block_ranges(n, B, one)
+        q8.quantize_blockwise(tab, T_d, B, TQ, N)
+        q8.dequantize_blockwise(tab, TQ, N, B, TD)
+        which = "signed" if signed else "unsigned"
+        same_bits(N, N_ref, "quantize (%s map): block maxima" % which)
+        same_bits(TQ, TQ_ref, "quantize (%s map): codes" % which)
+        same_bits(TD, TD_ref, "dequantize (%s map)" % which)
+        del T_d
+    H.report("SGD (2 steps), quantize and dequantize (both maps) on 1e9 elements, B=2048: every weight, code, "
+             "block maximum and dequantized value identical to the oracle's")
