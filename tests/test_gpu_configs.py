@@ -483,3 +483,21 @@ def test_sgd_quantize_dequantize_one_billion_every_entry(q8, tabs):
         del T_d
     H.report("SGD (2 steps), quantize and dequantize (both maps) on 1e9 elements, B=2048: every weight, code, "
              "block maximum and dequantized value identical to the oracle's")
+
+
+@pytest.mark.parametrize("B", [64, 256, 4096])
+def test_block_size_sweep_one_billion_parameters_every_entry(q8, tabs, B):
+    """The block-size sweep of bench.py (--block-size on 10^9 parameters) at its two ends and at
+    the paper's alternative B = 256: Adam, two steps, every entry against the oracle."""
+    n = 1_000_000_000
+    gen = torch.Generator(device="cuda"); gen.manual_seed(64 + B)
+    w = torch.empty(n, device="cuda").uniform_(-0.1, 0.1, generator=gen)
+    g = torch.empty(n, device="cuda")
+    d = device_state(n, B)
+    chk = H.WholeTensorParity("B=%d" % B, w, B)
+    for t in (1, 2):
+        g.normal_(0.0, 1e-3, generator=gen)
+        chk.oracle_step(g, t)
+        q8.adam8bit_step(w, g, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=t)
+        chk.compare(w, d, "B=%d step %d" % (B, t))
+    H.report_parity("1e9 parameters, B=%d, 2 steps, every entry after every step" % B, [chk])
