@@ -326,6 +326,21 @@ def test_more_than_2_31_elements(q8, tabs):
     check_block_properties("2^31+ elements", d, n, B)
 
 
+def test_more_than_2_31_elements_every_entry(q8, tabs):
+    """The same tensor of 2^31 + 2^20 + 777 elements, one Adam step, every entry against the
+    oracle (the host threads split the blocks): no element index is lost beyond 32 bits."""
+    n, B = (1 << 31) + (1 << 20) + 777, 2048
+    gen = torch.Generator(device="cuda"); gen.manual_seed(32)
+    w = torch.empty(n, device="cuda").uniform_(-0.1, 0.1, generator=gen)
+    g = torch.empty(n, device="cuda").normal_(0.0, 1e-3, generator=gen)
+    d = device_state(n, B)
+    chk = H.WholeTensorParity("2^31+ elements", w, B)
+    chk.oracle_step(g, 1)
+    q8.adam8bit_step(w, g, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **H.ADAM, t=1)
+    chk.compare(w, d, "2^31+ elements")
+    H.report_parity("2^31 + 2^20 + 777 parameters, B=2048, 1 step, every entry", [chk])
+
+
 def heavy_tail_grad_device(n, B, scale, gen):
     z = torch.randn(n, device="cuda", generator=gen)
     chi = torch.randn(3, n, device="cuda", generator=gen).pow_(2).sum(0).div_(3.0).sqrt_()
