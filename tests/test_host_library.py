@@ -26,6 +26,40 @@ def test_library_exports_every_declared_symbol():
     assert q8opt.status_str(0) == "Q8_OK" and "Q8_EBLOCK" in q8opt.status_str(q8opt.EBLOCK)
 
 
+def test_binding_argument_lists_follow_the_header():
+    """Every entry point's ctypes argument list has the kinds the header declares, in order:
+    pointer, 64-bit integer, int, float (a swapped pair would still load and run)."""
+    hdr = open(os.path.join(ROOT, "include", "q8opt.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", " ", hdr, flags=re.S)                 # comments carry commas and names
+
+    def kind_of_decl(d):
+        d = d.strip()
+        if "*" in d:
+            return "ptr"
+        if d.startswith("int64_t"):
+            return "i64"
+        if d.startswith("float"):
+            return "f32"
+        if d.startswith("int ") or d.startswith("q8_status"):
+            return "i32"
+        raise AssertionError("unexpected parameter declaration: %r" % d)
+
+    def kind_of_ctype(t):
+        if t is C.c_void_p or (isinstance(t, type) and issubclass(t, C._Pointer)):
+            return "ptr"
+        return {C.c_int64: "i64", C.c_int: "i32", C.c_float: "f32"}[t]
+
+    L = q8opt.lib()
+    seen = 0
+    for m in re.finditer(r"Q8_API\s+[^;(]*?\b(q8_[a-z0-9_]+)\s*\(([^;]*?)\)\s*;", hdr, flags=re.S):
+        name, params = m.group(1), m.group(2).strip()
+        declared = [] if params == "void" else [kind_of_decl(d) for d in params.split(",")]
+        bound = [kind_of_ctype(t) for t in getattr(L, name).argtypes]
+        assert bound == declared, name
+        seen += 1
+    assert seen == len(q8opt.EXPORTS)
+
+
 @pytest.mark.parametrize("signed", [True, False])
 def test_codebook_bit_equal_to_oracle(signed):
     assert np.array_equal(q8opt.build_codebook(signed).view(np.uint32), oracle.build_codebook(signed).view(np.uint32))
