@@ -97,6 +97,40 @@ def test_noalloc_equals_plan_on_two_calls_in_a_row(q8, tabs, B):
         lists[name][3].destroy()
 
 
+def test_noalloc_recorded_by_stream_capture(q8, tabs):
+    """The call enqueues kernels only (no allocation, memset or copy), so stream capture can
+    record it: a graph holding one call over 50 tensors (two table-fill launches and the step)
+    is replayed four times with eager gradient updates in between; after every replay the
+    result equals the plan-based entry point run eagerly on a copy."""
+    B = 2048
+    sizes = [3 * B + 1, 100_003, 33, 4096, 5 * 4096 + 3] + [900 + 41 * k for k in range(45)]
+    host, a, b = make_list(sizes, B, 13)
+    plan = q8.Plan(b, B)
+    hp = dict(H.ADAM, weight_decay=0.01, flags=q8.FLAG_DECOUPLED_WD)
+    # eager first calls on a side stream, as torch asks before a capture (they also fill the
+    # library's per-device caches: workspace address, occupancy)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        q8.multi_adam8bit_step_noalloc(a, B, tabs[0], tabs[1], **hp)
+    torch.cuda.current_stream().wait_stream(s)
+    plan.multi_adam8bit_step(tabs[0], tabs[1], **hp)
+    torch.cuda.synchronize()
+    same("eager call before the capture", a, b)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        q8.multi_adam8bit_step_noalloc(a, B, tabs[0], tabs[1], **hp)
+    for rep in range(1, 5):
+        for i, (x, y) in enumerate(zip(a, b)):                    # eager work between replays: fresh gradients
+            g = torch.from_numpy(synth.normal_grad(13, i, 1 + rep, x["g"].numel(), 1e-3)).cuda()
+            x["g"].copy_(g); y["g"].copy_(g)
+        graph.replay()
+        plan.multi_adam8bit_step(tabs[0], tabs[1], **hp)
+        torch.cuda.synchronize()
+        same("replay %d" % rep, a, b)
+    plan.destroy()
+
+
 def test_noalloc_limits_and_arguments(q8, tabs):
     L = q8.lib()
     w = torch.zeros(4096, device="cuda"); g = torch.zeros(4096, device="cuda")
