@@ -173,3 +173,22 @@ def test_square_root_with_every_seed(chk):
     first = C.c_int64(-1)
     bad = chk.check_sqrt_seeds(r.ctypes.data, r.size, C.byref(first))
     assert bad == 0, "%d mismatches, first r=%r" % (bad, r[first.value])
+
+
+def test_square_root_exhaustively_over_the_guarded_range(chk):
+    """Every binary32 r in [2^-80, 2^40] (1 006 632 961 values), each with every admissible seed:
+    the kernels' square root equals the IEEE one on the whole range their range test admits."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    def one_binade(e):
+        bits = np.uint32((e + 127) << 23) + np.arange(1 << 23, dtype=np.uint32)
+        r = bits.view(f32)
+        first = C.c_int64(-1)
+        bad = chk.check_sqrt_seeds(r.ctypes.data, r.size, C.byref(first))
+        return e, int(bad), (float(r[first.value]) if bad else None)
+    with ThreadPoolExecutor(max(1, min(8, os.cpu_count() or 1))) as ex:       # the C loop releases the GIL
+        for e, bad, where in ex.map(one_binade, range(-80, 40)):
+            assert bad == 0, "binade 2^%d: %d mismatches, first r=%r" % (e, bad, where)
+    top = np.array([2.0 ** 40], f32)
+    first = C.c_int64(-1)
+    assert chk.check_sqrt_seeds(top.ctypes.data, 1, C.byref(first)) == 0
