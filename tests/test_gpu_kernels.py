@@ -1,6 +1,8 @@
 """GPU parity of the stand-alone kernels and of the single-tensor steps against the CPU
 oracle, element by element: codes and absmax bit-exact, parameters within 1e-6 relative
 (the bar stated for this path).  Every call goes through the C ABI."""
+import os
+
 import numpy as np
 import pytest
 
@@ -395,6 +397,45 @@ def test_weight_update_division_by_all_ones_mantissas(q8, tabs):
     got = w.cpu().numpy()
     assert np.array_equal(got.view(np.uint32), w_ref.view(np.uint32)), np.flatnonzero(got != w_ref)[:8]
     H.assert_state_equal("states", d, st, w, w_ref)
+
+
+SQRT_BINADES = os.environ.get("Q8_SQRT_BINADES", "-80,-41,-1,0,1,39")      # "all" = every binade of the guarded range
+
+
+def test_weight_update_root_over_whole_binades(q8, tabs):
+    """The square root of the weight update on EVERY binary32 r of whole binades, end to end on
+    the device: beta1 = beta2 = 1 and g = 0 leave the states where they are, codes of 1.0 and a
+    block maximum N_r[b] = r make the dequantized second state any value wanted; with B = 64 one
+    launch covers a binade (2^23 blocks), each block pairing its r with 64 different first
+    states (64 codes of the signed map), eps = 0, alpha = 1, w = 0: w becomes -(m / sqrt(r)),
+    64 quotients per root, all compared with the oracle's IEEE results bit for bit.
+    Q8_SQRT_BINADES=all runs all 120 binades of [2^-80, 2^40] (10^9 roots, 6 * 10^10 quotients)."""
+    B = 64
+    binades = range(-80, 40) if SQRT_BINADES == "all" else [int(x) for x in SQRT_BINADES.split(",")]
+    nb = 1 << 23
+    n = nb * B
+    hp = dict(alpha=1.0, beta1=1.0, beta2=1.0, eps=0.0)
+    codes = np.concatenate([np.arange(0, 127, 4), np.arange(129, 256, 4)]).astype(np.uint8)     # 64 codes, none of them 0.0
+    assert codes.size == B
+    m_q0 = np.tile(codes, nb)
+    g_d = torch.zeros(n, device="cuda")
+    for e in binades:
+        r_vals = (np.uint32((e + 127) << 23) + np.arange(nb, dtype=np.uint32)).view(np.float32)
+        # first states around sqrt(r), so that the quotients stay well inside the binary32 range
+        N_m0 = np.ldexp(np.float32(1), np.full(nb, e // 2)).astype(np.float32)
+        st = dict(m_q=m_q0.copy(), r_q=np.full(n, 255, np.uint8), N_m=N_m0.copy(), N_r=r_vals.copy())
+        w_ref = np.zeros(n, np.float32)
+        w = torch.zeros(n, device="cuda"); d = {k: dev(v) for k, v in st.items()}
+        q8.adam8bit_step(w, g_d, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **hp)
+        H.oracle_adam8(w_ref, np.zeros(n, np.float32), st, B, hp=hp)
+        ref = torch.from_numpy(w_ref).cuda()
+        bad = int((w.view(torch.int32) != ref.view(torch.int32)).sum())
+        assert bad == 0, "binade 2^%d: %d of %d quotients differ" % (e, bad, n)
+        for k in ("m_q", "r_q", "N_m", "N_r"):
+            assert torch.equal(d[k].view(torch.uint8), torch.from_numpy(st[k]).cuda().view(torch.uint8)), (e, k)
+        del w, d, ref
+    H.report("square root and division of the weight update on every r of %d whole binades (%d roots, 64 quotients each): "
+             "identical to the oracle's" % (len(binades), len(binades) * nb))
 
 
 def test_host_threads_launch_concurrently(q8, tabs):
