@@ -438,6 +438,59 @@ def test_weight_update_root_over_whole_binades(q8, tabs):
              "identical to the oracle's" % (len(binades), len(binades) * nb))
 
 
+def _quantize_threaded(q, T, B):
+    """oracle.quantize_blockwise over disjoint block ranges on the host threads."""
+    n = T.size
+    nb = oracle.nblocks(n, B)
+    TQ = np.empty(n, np.uint8); N = np.empty(nb, np.float32)
+    nthr = H.host_threads()
+    per = -(-nb // nthr)
+
+    def run(k):
+        b0, b1 = k * per, min(nb, (k + 1) * per)
+        if b0 < b1:
+            e = slice(b0 * B, min(n, b1 * B))
+            TQ[e], N[b0:b1] = oracle.quantize_blockwise(q, T[e], B)
+    list(H.pool().map(run, range(nthr)))
+    return TQ, N
+
+
+@pytest.mark.parametrize("nbits", [0x3F800000, 0x2B7FFFFF, 0x4E2C9A35], ids=["N=1", "N=all-ones*2^-41", "N=7.2e8"])
+def test_quantize_every_value_under_a_block_maximum(q8, tabs, nbits):
+    """Normalisation by the block maximum and nearest-code search on EVERY binary32 value a block
+    with maximum N can hold: each block starts with N itself and continues with 2047 consecutive
+    bit patterns; the signed map sees all values of [-N, N] (2 * (bits(N) + 1), about 2 * 10^9),
+    the unsigned map all of [0, N].  Codes and block maxima against the oracle, bit for bit."""
+    B = 2048
+    N = np.array([nbits], np.uint32).view(np.float32)[0]
+    count = int(nbits) + 1                                        # non-negative values <= N
+    per = B - 1
+    nblk = -(-count // per)
+    chunk_blocks = 1 << 17                                        # 2.7e8 elements per piece
+    for signed, tab, q in ((True, tabs[0], H.codebooks()[0]), (False, tabs[1], H.codebooks()[1])):
+        for sign in ((0, 1) if signed else (0,)):
+            for b0 in range(0, nblk, chunk_blocks):
+                b1 = min(nblk, b0 + chunk_blocks)
+                pat = np.arange(b0 * per, b1 * per, dtype=np.int64)
+                pat = np.minimum(pat, count - 1).astype(np.uint32)           # the tail repeats N
+                T = np.empty((b1 - b0, B), np.uint32)
+                T[:, 0] = nbits
+                T[:, 1:] = pat.reshape(b1 - b0, per)
+                T = T.reshape(-1)
+                if sign:
+                    T[np.arange(T.size) % B != 0] |= np.uint32(0x80000000)   # the maximum itself stays +N
+                T = T.view(np.float32)
+                TQ_ref, N_ref = _quantize_threaded(q, T, B)
+                TQ = torch.empty(T.size, dtype=torch.uint8, device="cuda"); Nd = torch.empty(b1 - b0, device="cuda")
+                q8.quantize_blockwise(tab, dev(T), B, TQ, Nd)
+                assert torch.equal(Nd.view(torch.int32), torch.from_numpy(N_ref).cuda().view(torch.int32))
+                bad = int((TQ != torch.from_numpy(TQ_ref).cuda()).sum())
+                assert bad == 0, "%s map, sign %d, blocks [%d, %d): %d codes differ" % (
+                    "signed" if signed else "unsigned", sign, b0, b1, bad)
+    H.report("quantize: every binary32 value under the block maximum %.9g (%d patterns per sign), both maps: "
+             "codes identical to the oracle's" % (float(N), count))
+
+
 def test_host_threads_launch_concurrently(q8, tabs):
     """Four host threads, each with its own stream and tensor, call the library at the same time
     (ctypes releases the GIL during the call): the per-device records and occupancy caches are
