@@ -2,6 +2,8 @@
 extension outside the paper) against the CPU oracle: stored weights, codes and absmax all
 bit-exact -- the arithmetic is the binary32 step, and the one rounding of the new weight
 is decided in binary32 on both sides."""
+import os
+
 import numpy as np
 import pytest
 
@@ -277,3 +279,39 @@ def test_f16_one_billion_parameters_every_entry(q8, tabs):
             assert bad == 0, "step %d: %d stored weights differ in [%d, %d)" % (t, bad, lo, hi)
     H.report("f16 storage, 1e9 parameters, B=2048, 3 steps (AdamW with bias correction): every stored weight, "
              "code and block maximum identical to the oracle's")
+
+
+ROUND_BINADES = os.environ.get("Q8_ROUND_BINADES", "-26,-25,-24,-15,-14,0,15,16")      # "all" = every binade of [2^-80, 2^40]
+
+
+def test_f16_rounding_of_the_new_weight_over_whole_binades(q8, tabs):
+    """The one rounding of the new weight to the storage type, on dense sets of binary32 values:
+    beta1 = beta2 = 1 and g = 0 keep the states, codes of 1.0 with N_r = 1 make the denominator
+    1, so with alpha = 1 and w = 0 the stored weight is the rounding of -(Q[code] * N_m).  One
+    launch takes every binary32 N_m of a binade (2^23 blocks of 64) times 64 codes; stored
+    weights, codes and block maxima against the oracle, bit for bit.  Q8_ROUND_BINADES=all runs
+    the 120 binades of [2^-80, 2^40]."""
+    B = 64
+    binades = range(-80, 40) if ROUND_BINADES == "all" else [int(x) for x in ROUND_BINADES.split(",")]
+    nb = 1 << 23
+    n = nb * B
+    hp = dict(alpha=1.0, beta1=1.0, beta2=1.0, eps=0.0)
+    codes = np.concatenate([np.arange(0, 127, 4), np.arange(129, 256, 4)]).astype(np.uint8)
+    m_q0 = np.tile(codes, nb)
+    zeros16 = np.zeros(n, np.uint16)
+    g_d = torch.zeros(n, dtype=torch.float16, device="cuda")
+    for e in binades:
+        N_m0 = (np.uint32((e + 127) << 23) + np.arange(nb, dtype=np.uint32)).view(np.float32)
+        st = dict(m_q=m_q0.copy(), r_q=np.full(n, 255, np.uint8), N_m=N_m0.copy(), N_r=np.ones(nb, np.float32))
+        w_ref = zeros16.copy()
+        w = torch.zeros(n, dtype=torch.float16, device="cuda"); d = dev_state(st)
+        q8.adam8bit_step_f16(w, g_d, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **hp)
+        H.oracle_adam8(w_ref, zeros16, st, B, hp=hp, f16=True)
+        bad = int((w.view(torch.int16) != torch.from_numpy(w_ref.view(np.int16)).cuda()).sum())
+        assert bad == 0, "binade 2^%d: %d of %d stored weights differ" % (e, bad, n)
+        print("binade 2^%d done" % e, flush=True)                 # progress for the long run (pytest -s)
+        for k in ("m_q", "r_q", "N_m", "N_r"):
+            assert torch.equal(d[k].view(torch.uint8), torch.from_numpy(st[k]).cuda().view(torch.uint8)), (e, k)
+        del w, d
+    H.report("f16: rounding of the new weight on %d whole binades of first states (%d values each): identical to "
+             "the oracle's" % (len(binades), n))

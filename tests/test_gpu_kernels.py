@@ -431,6 +431,7 @@ def test_weight_update_root_over_whole_binades(q8, tabs):
         ref = torch.from_numpy(w_ref).cuda()
         bad = int((w.view(torch.int32) != ref.view(torch.int32)).sum())
         assert bad == 0, "binade 2^%d: %d of %d quotients differ" % (e, bad, n)
+        print("binade 2^%d done" % e, flush=True)                 # progress for the long run (pytest -s)
         for k in ("m_q", "r_q", "N_m", "N_r"):
             assert torch.equal(d[k].view(torch.uint8), torch.from_numpy(st[k]).cuda().view(torch.uint8)), (e, k)
         del w, d, ref
