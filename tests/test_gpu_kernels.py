@@ -399,22 +399,26 @@ def test_weight_update_division_by_all_ones_mantissas(q8, tabs):
     H.assert_state_equal("states", d, st, w, w_ref)
 
 
-SQRT_BINADES = os.environ.get("Q8_SQRT_BINADES", "-80,-41,-1,0,1,39")      # "all" = every binade of the guarded range
+SQRT_BINADES = os.environ.get("Q8_SQRT_BINADES", "-80,-1,0,39")      # "all" = every binade of the guarded range
 
 
-def test_weight_update_root_over_whole_binades(q8, tabs):
+@pytest.mark.parametrize("eps,flags,t", [(0.0, 0, 1), (1e-8, 1, 3)], ids=["plain", "bias-corrected"])
+def test_weight_update_root_over_whole_binades(q8, tabs, eps, flags, t):
     """The square root of the weight update on EVERY binary32 r of whole binades, end to end on
     the device: beta1 = beta2 = 1 and g = 0 leave the states where they are, codes of 1.0 and a
     block maximum N_r[b] = r make the dequantized second state any value wanted; with B = 64 one
     launch covers a binade (2^23 blocks), each block pairing its r with 64 different first
     states (64 codes of the signed map), eps = 0, alpha = 1, w = 0: w becomes -(m / sqrt(r)),
-    64 quotients per root, all compared with the oracle's IEEE results bit for bit.
+    64 quotients per root, all compared with the oracle's IEEE results bit for bit.  The second
+    case adds eps = 1e-8 and the bias-correction factors of step 3 (root scaled before eps is added).
     Q8_SQRT_BINADES=all runs all 120 binades of [2^-80, 2^40] (10^9 roots, 6 * 10^10 quotients)."""
     B = 64
     binades = range(-80, 40) if SQRT_BINADES == "all" else [int(x) for x in SQRT_BINADES.split(",")]
     nb = 1 << 23
     n = nb * B
-    hp = dict(alpha=1.0, beta1=1.0, beta2=1.0, eps=0.0)
+    hp = dict(alpha=1.0, beta1=1.0, beta2=1.0, eps=eps)
+    if flags:
+        hp.update(beta1=0.9, beta2=0.999)      # bias correction needs beta < 1; g = 0 then shrinks the states by beta
     codes = np.concatenate([np.arange(0, 127, 4), np.arange(129, 256, 4)]).astype(np.uint8)     # 64 codes, none of them 0.0
     assert codes.size == B
     m_q0 = np.tile(codes, nb)
@@ -426,8 +430,8 @@ def test_weight_update_root_over_whole_binades(q8, tabs):
         st = dict(m_q=m_q0.copy(), r_q=np.full(n, 255, np.uint8), N_m=N_m0.copy(), N_r=r_vals.copy())
         w_ref = np.zeros(n, np.float32)
         w = torch.zeros(n, device="cuda"); d = {k: dev(v) for k, v in st.items()}
-        q8.adam8bit_step(w, g_d, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, **hp)
-        H.oracle_adam8(w_ref, np.zeros(n, np.float32), st, B, hp=hp)
+        q8.adam8bit_step(w, g_d, d["m_q"], d["r_q"], d["N_m"], d["N_r"], tabs[0], tabs[1], B, t=t, flags=flags, **hp)
+        H.oracle_adam8(w_ref, np.zeros(n, np.float32), st, B, t=t, flags=flags, hp=hp)
         ref = torch.from_numpy(w_ref).cuda()
         bad = int((w.view(torch.int32) != ref.view(torch.int32)).sum())
         assert bad == 0, "binade 2^%d: %d of %d quotients differ" % (e, bad, n)
@@ -435,8 +439,8 @@ def test_weight_update_root_over_whole_binades(q8, tabs):
         for k in ("m_q", "r_q", "N_m", "N_r"):
             assert torch.equal(d[k].view(torch.uint8), torch.from_numpy(st[k]).cuda().view(torch.uint8)), (e, k)
         del w, d, ref
-    H.report("square root and division of the weight update on every r of %d whole binades (%d roots, 64 quotients each): "
-             "identical to the oracle's" % (len(binades), len(binades) * nb))
+    H.report("square root and division of the weight update (eps=%g, flags=%d) on every r of %d whole binades "
+             "(%d roots, 64 quotients each): identical to the oracle's" % (eps, flags, len(binades), len(binades) * nb))
 
 
 def _quantize_threaded(q, T, B):
