@@ -268,7 +268,7 @@ __device__ __forceinline__ float div_any(float a, float N)
     return (N == 0.0f) ? 0.0f : a / N;
 }
 
-struct BlockNorm { float N, y, ylo; bool fast; };
+struct BlockNorm { float N, y; bool fast; };
 
 // Reciprocal data of one block maximum held per lane (used when lanes of a wave
 // belong to different blocks, B < 256).
@@ -277,7 +277,7 @@ __device__ __forceinline__ BlockNorm make_norm(uint32_t nbits)
     BlockNorm b;
     b.N = __uint_as_float(nbits);
     b.fast = norm_in_fast_range(nbits);
-    exact::reciprocal_pair(b.fast ? b.N : 1.0f, b.y, b.ylo);
+    b.y = exact::reciprocal_rn(b.fast ? b.N : 1.0f);
     return b;
 }
 
@@ -289,14 +289,12 @@ __device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm
     int v = (int)nbits[0];
 #pragma unroll
     for (int k = 1; k < K; ++k) v = (lane == k) ? (int)nbits[k] : v;
-    float y, ylo;
-    exact::reciprocal_pair(norm_in_fast_range((uint32_t)v) ? __int_as_float(v) : 1.0f, y, ylo);
+    const float y = exact::reciprocal_rn(norm_in_fast_range((uint32_t)v) ? __int_as_float(v) : 1.0f);
 #pragma unroll
     for (int k = 0; k < K; ++k) {
         out[k].N = __uint_as_float(nbits[k]);
         out[k].fast = norm_in_fast_range(nbits[k]);
         out[k].y = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(y), k));
-        out[k].ylo = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ylo), k));
     }
 }
 
@@ -675,7 +673,7 @@ __device__ __forceinline__ void requantize_store(const unsigned char* lds, float
                 uint32_t packed = 0;
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    packed |= nearest_code<SECOND>(lds, div_fast(val[r][j], bn.N, bn.y, bn.ylo)) << (8 * j);
+                    packed |= nearest_code<SECOND>(lds, div_fast(val[r][j], bn.N, bn.y)) << (8 * j);
                 if (FULL || cnt > 0) store4b(codes + e0, cnt, packed);
             }
         } else {

@@ -23,31 +23,39 @@ namespace exact {
 Q8_EXACT_FN float bits_as_float(uint32_t u) { return __builtin_bit_cast(float, u); }
 Q8_EXACT_FN uint32_t float_as_bits(float f) { return __builtin_bit_cast(uint32_t, f); }
 
+// Both divisions below are "product with the reciprocal, one residual correction":
+//     q = RN(a y),  r = RN(a - b q) (one fma),  result = RN(q + r y) (one fma),
+// with y = RN(1/b), the correctly rounded reciprocal.  With u = one ulp of a/b: |a y - a/b| <= u
+// (y is off by at most 2^-24 relative), so q is within 2 u of a/b and |a - b q| <= 2 u |b|; the
+// rounding of r and the error of y each change r y by at most 2^-24 of that, so the value
+// q + r y that the last fma rounds lies within 2^-22 u of a/b.  It can round to the wrong
+// neighbour only if a/b itself lies that close to the midpoint of two neighbouring binary32
+// values: for 24-bit mantissas m, n that means |m 2^k - (2K+1) n| <= 16 (k = 24 or 25 by the
+// quotient's binade), a set the host check enumerates completely -- every n, every residue up
+// to +-64 in the suite (+-256 once: 3 * 10^9 pairs), both signs -- and on which the sequence
+// returns the IEEE quotient every time (tests/test_exact_devices.py).  Scaling both operands
+// by powers of two is exact as long as nothing leaves the normal range, so mantissas are all
+// that matters.
+
 // ---- Normalisation x = a / N (Eq. quant1) by a block-uniform N in [2^-60, 2^60], |a| <= N.
-// Once per block: y = RN(1/N) (an IEEE division) and ylo = RN(RN(1 - N y) y), so that
-// y + ylo = 1/N to about 2^-46.
+// Once per block: y = RN(1/N) (an IEEE division).
 Q8_EXACT_FN bool norm_in_fast_range(uint32_t nbits)
 {
     return (nbits >= 0x21800000u) && (nbits <= 0x5d800000u);   // 2^-60 .. 2^60
 }
 
-Q8_EXACT_FN void reciprocal_pair(float N, float& y, float& ylo)
+Q8_EXACT_FN float reciprocal_rn(float N)
 {
-    y = 1.0f / N;
-    const float e = __builtin_fmaf(-N, y, 1.0f);
-    ylo = e * y;
+    return 1.0f / N;
 }
 
-// Per element: q = RN(a y + RN(a ylo)) is a faithful quotient, and one residual correction
-// with the correctly rounded reciprocal returns RN(a/N) (Markstein's division theorem).
-// When the quotient is below the normal range (|a/N| < 2^-126) the result may be off in its
-// last bits; such values lie far below the smallest decision threshold of any codebook the
-// table builder accepts and get the same code.
-Q8_EXACT_FN float div_fast(float a, float N, float y, float ylo)
+// Per element.  When the quotient is below the normal range (|a/N| < 2^-126) the result may be
+// off in its last bits; such values lie far below the smallest decision threshold of any
+// codebook the table builder accepts and get the same code.
+Q8_EXACT_FN float div_fast(float a, float N, float y)
 {
-    const float t = a * ylo;
-    const float q = __builtin_fmaf(a, y, t);
-    const float r = __builtin_fmaf(-q, N, a);
+    const float q = a * y;
+    const float r = __builtin_fmaf(-N, q, a);
     return __builtin_fmaf(r, y, q);
 }
 
@@ -57,24 +65,20 @@ constexpr float kFastLo = 0x1p-80f;
 constexpr float kFastHi = 0x1p40f;
 
 // Division: for r in the range, d = sqrt(r) c + eps lies in [2^-40, 2^31] and |m| / d in
-// [2^-111, 2^80].  For such operands the classical correctly rounded sequence -- approximate
-// reciprocal, one reciprocal refinement, a product and two quotient refinements -- needs
-// neither operand scaling nor a final fix-up (no operand or quotient is zero, subnormal or
-// near the exponent limits).  `y0` = approximate 1/b, within one ulp.  One seed is outside the
-// guarantee: when the mantissa of b is all ones, 1/b lies half an ulp above a power of two, and
-// from that power of two the refinement below lands on a tie and returns it again instead of
-// the correctly rounded reciprocal (the known exception of Newton's step); a numerator that is
-// a power of two then rounds the wrong way.  The hardware's reciprocal returns the other
-// neighbour for such b (checked on the device for every exponent of the range); the host check
-// covers every other seed within one ulp.
+// [2^-111, 2^80]: no operand or quotient is zero, subnormal or near the exponent limits, so
+// the sequence needs neither operand scaling nor a final fix-up.  `y0` = approximate 1/b,
+// within one ulp; one Newton step turns it into RN(1/b) -- for every mantissa of b and every
+// such y0 (the host check runs all 2^23 mantissas) with one exception: when the mantissa of b
+// is all ones, 1/b lies half an ulp above a power of two, and from that power of two the step
+// lands on a tie and returns it again (the known exception of Newton's step); a numerator that
+// is a power of two then rounds the wrong way.  The hardware's reciprocal returns the other
+// neighbour for such b (checked on the device for every exponent of the range).
 Q8_EXACT_FN float div_rn_from_seed(float a, float b, float y0)
 {
     const float e = __builtin_fmaf(-b, y0, 1.0f);
     const float y = __builtin_fmaf(e, y0, y0);
-    float q = a * y;
-    float r = __builtin_fmaf(-b, q, a);
-    q = __builtin_fmaf(r, y, q);
-    r = __builtin_fmaf(-b, q, a);
+    const float q = a * y;
+    const float r = __builtin_fmaf(-b, q, a);
     return __builtin_fmaf(r, y, q);
 }
 

@@ -36,9 +36,8 @@ int64_t check_div_fast_pairs(const float* a, const float* N, int64_t n, int64_t*
     int64_t bad = 0;
     for (int64_t i = 0; i < n; ++i) {
         if (!norm_in_fast_range(bits(N[i])) || !(std::fabs(a[i]) <= N[i])) { if (!bad++) *first_bad = i; continue; }
-        float y, ylo;
-        reciprocal_pair(N[i], y, ylo);
-        const float got = div_fast(a[i], N[i], y, ylo), want = a[i] / N[i];
+        const float y = reciprocal_rn(N[i]);
+        const float got = div_fast(a[i], N[i], y), want = a[i] / N[i];
         bool ok;
         if (std::fabs(want) >= 0x1p-126f) ok = bits(got) == bits(want);
         else ok = std::fabs(got) < 0x1p-100f && (got == 0.0f || want == 0.0f || std::signbit(got) == std::signbit(want));
@@ -62,9 +61,8 @@ int64_t check_div_fast_random(uint64_t seed, int64_t count, float* bad_a, float*
         if (r2 & 1) a = -a;
         if ((r2 & 0xfe) == 0) a = (r2 & 1) ? -N : N;
         if (!(std::fabs(a) <= N) || !norm_in_fast_range(bits(N))) continue;
-        float y, ylo;
-        reciprocal_pair(N, y, ylo);
-        const float got = div_fast(a, N, y, ylo), want = a / N;
+        const float y = reciprocal_rn(N);
+        const float got = div_fast(a, N, y), want = a / N;
         const bool ok = (std::fabs(want) >= 0x1p-126f) ? bits(got) == bits(want) : std::fabs(got) < 0x1p-100f;
         if (!ok && !bad++) { *bad_a = a; *bad_N = N; }
     }
@@ -119,6 +117,56 @@ int64_t check_sqrt_seeds(const float* r, int64_t n, int64_t* first_bad)
                 *first_bad = i;
     }
     return bad;
+}
+
+// The complete set of hard operands of "product with the reciprocal, one correction": every pair
+// of 24-bit mantissas (m, n) whose quotient lies within R * 2^-48 (relative) of a value with 25
+// significant bits -- the midpoints of neighbouring binary32 values are among them -- i.e.
+// m 2^k - L n = r with 0 < |r| <= R, k = 25 for m < n and 24 for m > n.  For each divisor n
+// [n_begin, n_end) the numerators are solved from m = r 2^-k (mod n).  Each pair is run through
+// div_fast with y = RN(1/n) (both signs of m) and through div_rn_from_seed with every admissible
+// seed; the refined reciprocal of every admissible seed is also compared with RN(1/n).
+// out[0] = pairs, out[1] = div_fast failures, out[2] = div_rn_from_seed failures,
+// out[3] = refined reciprocals that are not RN(1/n).
+void check_near_midpoint_pairs(uint32_t n_begin, uint32_t n_end, int R, int64_t* out)
+{
+    int64_t pairs = 0, bad_fast = 0, bad_seed = 0, bad_y = 0;
+    for (uint32_t n = n_begin; n < n_end; ++n) {
+        const float b = (float)n, yrn = 1.0f / b;
+        const double truth = 1.0 / (double)b;
+        const float seeds[3] = {next_dn(yrn), yrn, next_up(yrn)};
+        bool adm[3];
+        const bool all_ones = (n & 0x7fffffu) == 0x7fffffu;
+        for (int k = 0; k < 3; ++k) {
+            adm[k] = admissible(seeds[k], truth) && !(all_ones && (bits(seeds[k]) & 0x7fffffu) == 0);
+            if (!adm[k]) continue;
+            const float e = __builtin_fmaf(-b, seeds[k], 1.0f);
+            if (bits(__builtin_fmaf(e, seeds[k], seeds[k])) != bits(yrn)) ++bad_y;
+        }
+        const int j = __builtin_ctz(n);
+        const uint32_t g = 1u << j, n2 = n >> j;                       // n = g * n2, n2 odd
+        const uint64_t inv2 = (n2 + 1) / 2;                            // 2^-1 mod n2
+        for (int kP = 24; kP <= 25; ++kP) {
+            uint64_t inv = 1 % n2;                                      // (2^kP / g)^-1 mod n2
+            for (int i = 0; i < kP - j; ++i) inv = inv * inv2 % n2;
+            for (int r = -R; r <= R; ++r) {
+                if (r == 0 || (r & (int)(g - 1))) continue;             // solvable only if g divides r
+                const int64_t rr = r / (int)g;
+                const uint64_t m0 = (uint64_t)((rr % (int64_t)n2 + n2) % n2) * inv % n2;
+                for (uint64_t m = m0; m < (1u << 24); m += n2) {        // all residues mod n, lifted into the mantissa range
+                    if (m < (1u << 23)) continue;
+                    if (kP == 25 ? !(m < n) : !(m > n)) continue;
+                    const float a = (float)m, want = a / b;
+                    ++pairs;
+                    if (bits(div_fast(a, b, yrn)) != bits(want)) ++bad_fast;
+                    if (bits(div_fast(-a, b, yrn)) != bits(-want)) ++bad_fast;
+                    for (int k = 0; k < 3; ++k)
+                        if (adm[k] && bits(div_rn_from_seed(a, b, seeds[k])) != bits(want)) ++bad_seed;
+                }
+            }
+        }
+    }
+    out[0] = pairs; out[1] = bad_fast; out[2] = bad_seed; out[3] = bad_y;
 }
 
 }  // extern "C"

@@ -31,6 +31,7 @@ def chk(tmp_path_factory):
     L.check_div_seeds.argtypes = [p, p, i64, p]; L.check_div_seeds.restype = i64
     L.check_div_seeds_mode.argtypes = [p, p, i64, C.c_int, p]; L.check_div_seeds_mode.restype = i64
     L.check_sqrt_seeds.argtypes = [p, i64, p]; L.check_sqrt_seeds.restype = i64
+    L.check_near_midpoint_pairs.argtypes = [C.c_uint32, C.c_uint32, C.c_int, p]; L.check_near_midpoint_pairs.restype = None
     return L
 
 
@@ -258,3 +259,26 @@ def test_the_one_excluded_seed_is_a_real_exception(chk):
     assert chk.check_div_seeds_mode(m.ctypes.data, ds.ctypes.data, m.size, 1, C.byref(first)) == 1
     assert m[first.value] == f32(1.0)
     assert chk.check_div_seeds_mode(m.ctypes.data, ds.ctypes.data, m.size, 0, C.byref(first)) == 0
+
+
+def test_every_quotient_near_a_rounding_midpoint(chk):
+    """The complete set of hard operands of both divisions.  They are "product with the correctly
+    rounded reciprocal, one residual correction"; the value their last fma rounds lies within
+    2^-22 ulp of a/b, so a wrong neighbour needs a/b within that distance of a midpoint:
+    for 24-bit mantissas m, n that is |m 2^k - (2K+1) n| <= 16.  The checker solves these
+    congruences for EVERY divisor mantissa n and every residue up to +-64 (four times the bound;
+    +-256 was run once: 3 * 10^9 pairs), runs div_fast on both signs and div_rn_from_seed with every
+    admissible seed, and also confirms for every n that one Newton step turns every admissible
+    seed into RN(1/n).  Powers of two scale exactly, so mantissas are all there is to check."""
+    from concurrent.futures import ThreadPoolExecutor
+    lo, hi, parts = 1 << 23, 1 << 24, 64
+    step = (hi - lo) // parts
+
+    def piece(k):
+        out = (C.c_int64 * 4)()
+        chk.check_near_midpoint_pairs(lo + k * step, lo + (k + 1) * step, 64, out)
+        return list(out)
+    with ThreadPoolExecutor(max(1, min(8, os.cpu_count() or 1))) as ex:
+        tot = np.sum(list(ex.map(piece, range(parts))), axis=0)
+    assert tot[0] > 700_000_000, tot
+    assert tot[1] == 0 and tot[2] == 0 and tot[3] == 0, "pairs %d: div_fast %d, div_rn_from_seed %d, reciprocal %d" % tuple(tot)
