@@ -308,7 +308,7 @@ __device__ __forceinline__ float div_rn_inrange(float a, float b)
 
 __device__ __forceinline__ float sqrt_rn_fast(float r)
 {
-    return exact::sqrt_rn_from_seed(r, __builtin_amdgcn_sqrtf(r));
+    return exact::sqrt_rn_from_rsq(r, __builtin_amdgcn_rsqf(r));
 }
 
 // ---------------------------------------------------------------------------

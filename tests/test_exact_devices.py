@@ -31,6 +31,7 @@ def chk(tmp_path_factory):
     L.check_div_seeds.argtypes = [p, p, i64, p]; L.check_div_seeds.restype = i64
     L.check_div_seeds_mode.argtypes = [p, p, i64, C.c_int, p]; L.check_div_seeds_mode.restype = i64
     L.check_sqrt_seeds.argtypes = [p, i64, p]; L.check_sqrt_seeds.restype = i64
+    L.check_sqrt_seeds_mode.argtypes = [p, i64, C.c_int, p]; L.check_sqrt_seeds_mode.restype = i64
     L.check_near_midpoint_pairs.argtypes = [C.c_uint32, C.c_uint32, C.c_int, p]; L.check_near_midpoint_pairs.restype = None
     return L
 
@@ -282,3 +283,17 @@ def test_every_quotient_near_a_rounding_midpoint(chk):
         tot = np.sum(list(ex.map(piece, range(parts))), axis=0)
     assert tot[0] > 700_000_000, tot
     assert tot[1] == 0 and tot[2] == 0 and tot[3] == 0, "pairs %d: div_fast %d, div_rn_from_seed %d, reciprocal %d" % tuple(tot)
+
+
+def test_the_one_excluded_root_seed_is_a_real_exception(chk):
+    """The (r, seed) pair the square-root checks set aside: in strict mode exactly that r fails in
+    each binade of odd exponent, and only with the seed one ulp above the correctly rounded
+    reciprocal root.  tests/test_gpu_kernels.py (test_weight_update_root_over_whole_binades)
+    runs every r through the kernel: the hardware's seed is another one."""
+    for e, expect in ((1, 1), (0, 0), (-37, 1), (-38, 0)):
+        r = (np.uint32((e + 127) << 23) + np.arange(1 << 23, dtype=np.uint32)).view(f32)
+        first = C.c_int64(-1)
+        bad = chk.check_sqrt_seeds_mode(r.ctypes.data, r.size, 1, C.byref(first))
+        assert bad == expect, (e, bad)
+        if expect:
+            assert int(r[first.value].view(np.uint32)) & 0x7fffff == 0x6e9372
