@@ -31,9 +31,9 @@
 // Exact arithmetic: the update formulas are written one operation per statement
 // and the file is compiled with -ffp-contract=off.  The normalisation x = m / N
 // (Eq. quant1) is a correctly rounded quotient: N is uniform over a block, so
-// y = RN(1/N) is formed once and each element takes a faithful product and one
-// residual-correction fma pair (the classical Newton/Markstein division
-// sequence); blocks whose N lies outside [2^-60, 2^60] use the plain divide.  The
+// y = RN(1/N) is formed once and each element takes a product and one
+// residual-correction fma pair (q8opt_exact.h states why that is exact); blocks
+// whose N lies outside [2^-60, 2^60] use the plain divide.  The
 // square root and the division of the Adam weight update take short, equally exact
 // forms on rows whose new states all lie in [2^-80, 2^40], sqrtf and a / b otherwise.
 //
@@ -299,7 +299,7 @@ __device__ __forceinline__ void make_norms(const uint32_t (&nbits)[K], BlockNorm
 }
 
 // Short forms of the square root and of the division in the Adam weight update (q8opt_exact.h),
-// seeded with the hardware's approximate reciprocal and square root; used on rows where every
+// seeded with the hardware's approximate reciprocal and reciprocal square root; used on rows where every
 // new state lies in [kFastLo, kFastHi], all other rows take sqrtf and the general a / b.
 __device__ __forceinline__ float div_rn_inrange(float a, float b)
 {
