@@ -395,7 +395,7 @@ template <> struct Wide<F16> { typedef gu16* ptr; typedef gcu16* cptr; };
 // one job per draw measured best.  With 16-bit storage it moves 10 instead of 16 bytes per
 // parameter and is bound by instruction issue: three workgroups per CU (24 waves, 80 VGPRs; the
 // 52 KB LDS map fits three times) measured 6 % faster there (3 % slower with binary32), two jobs
-// per draw another 1 % (7 % slower with binary32: a wider window of addresses in flight).
+// per draw another 2 % (7 % slower with binary32: a wider window of addresses in flight).
 template <typename WT> struct Occupancy { static constexpr int kWgPerCu = 2, kSpan = 1; };
 template <> struct Occupancy<Bf16> { static constexpr int kWgPerCu = 3, kSpan = 2; };
 template <> struct Occupancy<F16> { static constexpr int kWgPerCu = 3, kSpan = 2; };
