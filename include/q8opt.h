@@ -112,7 +112,8 @@ Q8_API q8_status q8_build_codebook(int is_signed, float* qmap_out /* host [256] 
  * host into `qtable_out` (q8_qtable_bytes() bytes, host); the caller copies the
  * bytes to 16-byte aligned device memory once and passes that device pointer
  * to the entry points below.  Any strictly increasing 256-entry codebook within
- * [-1, 1] is accepted as long as no bucket holds more than one threshold.
+ * [-1, 1] is accepted as long as no bucket holds more than one threshold and no
+ * non-zero entry is smaller than 2^-99 in magnitude (else Q8_ECODEBOOK).
  */
 Q8_API size_t    q8_qtable_bytes(void);
 Q8_API q8_status q8_build_qtable(const float* qmap /* host [256] */, void* qtable_out /* host */);

@@ -2,10 +2,10 @@
 // of the general a / b and sqrtf.  Plain functions of binary32 values built from fma, so that
 // the very same source compiles for the GPU (inside q8opt_device.h) and for the host, where
 // tests/test_exact_devices.py checks each of them against IEEE division and square root on
-// random, adversarial and threshold-hugging operands (no GPU needed).  The hardware's
-// approximate reciprocal and square root enter as arguments ("seed"): the host check feeds
-// every binary32 value within one unit in the last place of the true result, which covers
-// whatever the instruction returns.
+// random, adversarial and threshold-hugging operands and on complete enumerations of their hard
+// cases (no GPU needed).  The hardware's approximate reciprocal and reciprocal square root
+// enter as arguments ("seed"): the host check feeds every binary32 value within one unit in
+// the last place of the true result, which covers whatever the instruction returns.
 #ifndef Q8OPT_EXACT_H
 #define Q8OPT_EXACT_H
 
@@ -51,7 +51,7 @@ Q8_EXACT_FN float reciprocal_rn(float N)
 
 // Per element.  When the quotient is below the normal range (|a/N| < 2^-126) the result may be
 // off in its last bits; such values lie far below the smallest decision threshold of any
-// codebook the table builder accepts and get the same code.
+// codebook the table builder accepts (no non-zero entry below 2^-99) and get the same code.
 Q8_EXACT_FN float div_fast(float a, float N, float y)
 {
     const float q = a * y;

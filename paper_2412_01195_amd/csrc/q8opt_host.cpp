@@ -78,6 +78,9 @@ extern "C" q8_status q8_build_qtable(const float* qmap, void* qtable_out)
     for (int j = 0; j < 256; ++j) {
         if (!(qmap[j] >= -1.0f && qmap[j] <= 1.0f)) return Q8_ECODEBOOK;
         if (j && !(qmap[j] > qmap[j - 1])) return Q8_ECODEBOOK;
+        // every decision threshold stays far above the subnormal quotients, whose last bits the
+        // kernels' short division does not guarantee
+        if (qmap[j] != 0.0f && std::fabs(qmap[j]) < 0x1p-99f) return Q8_ECODEBOOK;
     }
     unsigned char* blob = static_cast<unsigned char*>(qtable_out);
     std::memset(blob, 0, kQTabBytes);

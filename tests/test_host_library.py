@@ -123,6 +123,18 @@ def test_qtable_accepts_other_codebooks_and_rejects_bad_ones():
     fine = np.sort(np.concatenate([[0.0], 1e-9 * np.arange(1, 256)])).astype(np.float32)   # too fine near zero
     with pytest.raises(q8opt.Q8Error):
         q8opt.build_qtable(fine)
+    # a non-zero entry below 2^-99 would put a decision threshold among quotients whose last bits
+    # the kernels' short division does not guarantee: refused; 2^-99 itself is accepted
+    for v, ok in ((2.0 ** -100, False), (1e-40, False), (-(2.0 ** -120), False), (2.0 ** -99, True)):
+        tiny = lin.copy()
+        tiny[127], tiny[128] = (0.0, np.float32(v)) if v > 0 else (np.float32(v), 0.0)
+        assert tiny[126] < tiny[127] < tiny[128] < tiny[129]
+        if ok:
+            q8opt.build_qtable(tiny)
+        else:
+            with pytest.raises(q8opt.Q8Error) as e:
+                q8opt.build_qtable(tiny)
+            assert e.value.status == q8opt.ECODEBOOK
 
 
 def test_argument_validation_needs_no_gpu():
