@@ -182,4 +182,32 @@ void check_near_midpoint_pairs(uint32_t n_begin, uint32_t n_end, int R, int64_t*
     out[0] = pairs; out[1] = bad_fast; out[2] = bad_seed; out[3] = bad_y;
 }
 
+// The same set of pairs as a list (for the device test): mantissas as integers in [2^23, 2^24).
+// Returns the number of pairs written (at most cap).
+int64_t list_near_midpoint_pairs(uint32_t n_begin, uint32_t n_end, int R, uint32_t* out_m, uint32_t* out_n, int64_t cap)
+{
+    int64_t count = 0;
+    for (uint32_t n = n_begin; n < n_end; ++n) {
+        const int j = __builtin_ctz(n);
+        const uint32_t g = 1u << j, n2 = n >> j;
+        const uint64_t inv2 = (n2 + 1) / 2;
+        for (int kP = 24; kP <= 25; ++kP) {
+            uint64_t inv = 1 % n2;
+            for (int i = 0; i < kP - j; ++i) inv = inv * inv2 % n2;
+            for (int r = -R; r <= R; ++r) {
+                if (r == 0 || (r & (int)(g - 1))) continue;
+                const int64_t rr = r / (int)g;
+                const uint64_t m0 = (uint64_t)((rr % (int64_t)n2 + n2) % n2) * inv % n2;
+                for (uint64_t m = m0; m < (1u << 24); m += n2) {
+                    if (m < (1u << 23)) continue;
+                    if (kP == 25 ? !(m < n) : !(m > n)) continue;
+                    if (count == cap) return count;
+                    out_m[count] = (uint32_t)m; out_n[count] = n; ++count;
+                }
+            }
+        }
+    }
+    return count;
+}
+
 }  // extern "C"

@@ -443,6 +443,75 @@ def test_weight_update_root_over_whole_binades(q8, tabs, eps, flags, t):
              "(%d roots, 64 quotients each): identical to the oracle's" % (eps, flags, len(binades), len(binades) * nb))
 
 
+HARD_DIVISORS = os.environ.get("Q8_HARD_DIVISORS", "262144")       # "all" = every divisor mantissa (2^23)
+
+
+def test_weight_update_division_on_every_hard_pair_of_many_divisors(q8, tabs, tmp_path):
+    """The hard operands of the weight update's division, through the kernel: for a range of
+    divisor mantissas n (2^18 of them in the suite, Q8_HARD_DIVISORS=all: all 2^23) every numerator
+    m whose quotient lies within 16 * 2^-48 of a rounding midpoint (the set the host check
+    enumerates, tests/exact_check.cpp).  One block of 64 per pair: codes of 1.0 with N_m = m 2^a
+    and N_r = RN((n 2^b)^2) make the first state the numerator and the root of the second the
+    divisor exactly; beta1 = beta2 = 1, g = 0, eps = 0, alpha = 1, w = 0 give w = -(m / d).  The
+    hardware's reciprocal, one Newton step and one residual correction must return the IEEE
+    quotient on every one of them."""
+    import ctypes as C
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    lib = str(tmp_path / "libexact_check.so")
+    subprocess.check_call(["g++", "-O2", "-std=c++20", "-ffp-contract=off", "-fno-fast-math", "-mfma", "-shared", "-fPIC",
+                           "-I" + os.path.join(root, "paper_2412_01195_amd", "csrc"),
+                           os.path.join(root, "tests", "exact_check.cpp"), "-o", lib])
+    L = C.CDLL(lib)
+    L.list_near_midpoint_pairs.argtypes = [C.c_uint32, C.c_uint32, C.c_int, C.c_void_p, C.c_void_p, C.c_int64]
+    L.list_near_midpoint_pairs.restype = C.c_int64
+    ndiv = (1 << 23) if HARD_DIVISORS == "all" else int(HARD_DIVISORS)
+    B, per_launch = 64, 1 << 24
+    hp = dict(alpha=1.0, beta1=1.0, beta2=1.0, eps=0.0)
+    rng = np.random.default_rng(99)
+    n0 = (1 << 23) + (int(rng.integers(0, (1 << 23) - ndiv + 1)) if ndiv < (1 << 23) else 0)
+    total = 0
+    step = 1 << 16                                                 # divisors per enumeration call
+    pend_m, pend_n = [], []
+
+    def run(mi, ni):
+        nonlocal total
+        k = mi.size
+        e_d = rng.integers(-40, 20, k)                             # d = n 2^(e_d - 23) in [2^-40, 2^20]
+        e_m = np.clip(e_d + rng.integers(-30, 30, k), -80, 38)
+        m = np.ldexp(mi.astype(np.float64), e_m - 23)              # positive: rounding to nearest is symmetric
+        d = np.ldexp(ni.astype(np.float64), e_d - 23)
+        st = dict(m_q=np.full(k * B, 255, np.uint8), r_q=np.full(k * B, 255, np.uint8),
+                  N_m=m.astype(np.float32), N_r=(d * d).astype(np.float32))     # sqrt(RN(d^2)) = d
+        w_ref = np.zeros(k * B, np.float32)
+        w = torch.zeros(k * B, device="cuda"); dd = {kk: dev(v) for kk, v in st.items()}
+        g0 = torch.zeros(k * B, device="cuda")
+        q8.adam8bit_step(w, g0, dd["m_q"], dd["r_q"], dd["N_m"], dd["N_r"], tabs[0], tabs[1], B, **hp)
+        want = -(m.astype(np.float32) / d.astype(np.float32))                  # IEEE quotient of the two binary32 operands
+        got = w.view(k, B)
+        ref = torch.from_numpy(want).cuda()
+        bad = int((got.view(torch.int32) != ref.view(torch.int32)[:, None]).sum())
+        assert bad == 0, "%d of %d quotients differ" % (bad, k * B)
+        H.oracle_adam8(w_ref, np.zeros(k * B, np.float32), st, B, hp=hp)       # and the oracle agrees with that
+        assert np.array_equal(w_ref.reshape(k, B)[:, 0].view(np.uint32), want.view(np.uint32))
+        total += k
+        print("%d pairs done" % total, flush=True)
+
+    for lo in range(n0, n0 + ndiv, step):
+        hi = min(n0 + ndiv, lo + step)
+        cap = (hi - lo) * 40
+        bm = np.empty(cap, np.uint32); bn = np.empty(cap, np.uint32)
+        cnt = L.list_near_midpoint_pairs(lo, hi, 16, bm.ctypes.data, bn.ctypes.data, cap)
+        assert 0 < cnt < cap
+        pend_m.append(bm[:cnt]); pend_n.append(bn[:cnt])
+        if sum(x.size for x in pend_m) >= per_launch:
+            run(np.concatenate(pend_m), np.concatenate(pend_n)); pend_m, pend_n = [], []
+    if pend_m:
+        run(np.concatenate(pend_m), np.concatenate(pend_n))
+    H.report("weight-update division on every near-midpoint numerator of %d divisor mantissas (%d pairs): identical to "
+             "the IEEE quotient" % (ndiv, total))
+
+
 def _quantize_threaded(q, T, B):
     """oracle.quantize_blockwise over disjoint block ranges on the host threads."""
     n = T.size
