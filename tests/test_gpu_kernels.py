@@ -456,7 +456,10 @@ def test_weight_update_division_on_every_hard_pair_of_many_divisors(q8, tabs, tm
     hardware's reciprocal, one Newton step and one residual correction must return the IEEE
     quotient on every one of them."""
     import ctypes as C
+    import shutil
     import subprocess
+    if shutil.which("g++") is None:
+        pytest.skip("no host compiler for the pair enumeration")
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     lib = str(tmp_path / "libexact_check.so")
     subprocess.check_call(["g++", "-O2", "-std=c++20", "-ffp-contract=off", "-fno-fast-math", "-mfma", "-shared", "-fPIC",
